@@ -1,0 +1,148 @@
+/* preserve.h - C ABI of the MI355X request-load-predictor + load-anticipator library.
+ *
+ * The library implements the per-request hot path of PreServe's prediction-based management:
+ *   - the request load predictor (paper Sec. 3.3 "Tier-2: Request Load Prediction"): prompt
+ *     token ids -> predicted number of response tokens, by a DistilBERT-shaped encoder whose
+ *     [CLS] state feeds a two-layer regression head, with M learnable prompt vectors appended
+ *     to the text tokens;
+ *   - the instance load anticipator (paper Sec. 3.4.1 "Instance Load Anticipator"): per-request
+ *     predictions -> per-instance future-load curves, updated per request.
+ *
+ * Conventions
+ *   - Every array argument is a DEVICE pointer unless marked "host".  The caller owns every
+ *     buffer it passes in, including workspaces; the library allocates device memory only in
+ *     ps_model_load() and releases it in ps_model_free().
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the default
+ *     stream) and return without synchronising.  Outputs of one call may be passed to the
+ *     next call on the same stream (pred_tokens of ps_predict_load -> ps_anticipate).
+ *   - Return value: PS_OK or a negative PS_E* code for faults the host can see.  Faults only
+ *     visible in device data are recorded in a caller-provided ps_status block (below).
+ *   - One model may be used from one stream at a time; calls sharing a workspace must be
+ *     ordered by the caller.
+ */
+#ifndef PRESERVE_H
+#define PRESERVE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PS_OK            0
+#define PS_EINVAL       -1   /* null pointer, negative size, inconsistent arguments          */
+#define PS_EIO          -2   /* model file cannot be read                                    */
+#define PS_EFORMAT      -3   /* model file header or size is wrong                           */
+#define PS_ENOMEM       -4   /* host or device allocation failed                             */
+#define PS_EWORKSPACE   -5   /* workspace too small or misaligned (256 B)                    */
+#define PS_EUNSUPPORTED -6   /* shape outside what the kernels are built for                 */
+#define PS_EHIP         -7   /* a HIP runtime call failed                                    */
+
+/* Device-side fault record.  The caller zeroes it (device memory, 16 bytes, 8-byte aligned)
+ * before a call or a series of calls and reads it back with ps_status_read().  `flags` is the
+ * OR of PS_ST_* bits.  `first_bad`, as ps_status_read() returns it, is the smallest request /
+ * record index that raised one, or -1 if none carried an index; in device memory the field
+ * holds an encoding of it that only ps_status_read() interprets. */
+typedef struct ps_status {
+    int32_t flags;
+    int32_t reserved;
+    int64_t first_bad;
+} ps_status;
+
+#define PS_ST_BAD_TOKEN    0x01  /* token id outside [0, vocab)                               */
+#define PS_ST_BAD_LENGTH   0x02  /* request length < 1, > its span, or + n_soft > max_pos     */
+#define PS_ST_NAN          0x04  /* a prediction is NaN                                       */
+#define PS_ST_BAD_RECORD   0x10  /* anticipator record skipped: pred_tokens < 0 or > PS_MAX_PRED,
+                                    instance outside [0, n_inst), arrival outside [0, horizon),
+                                    or rate[instance] < 1                                     */
+#define PS_ST_RANGE        0x20  /* a load bucket left the int32 range (its low 32 bits are stored),
+                                    or a workgroup folded so many tokens (2^27 per wavefront)
+                                    that it cannot rule that out                              */
+
+#define PS_MAX_PRED  (1 << 24)   /* largest pred_tokens value ps_anticipate accepts           */
+
+typedef struct ps_model ps_model;   /* opaque; owns the device copy of the weights */
+
+typedef struct ps_model_info {
+    int32_t layers, hidden, heads, ffn, vocab, max_pos, n_soft, head_hidden;
+    int32_t dtype;     /* 0 = fp32 weights and arithmetic, 1 = bf16 storage / fp32 accumulate */
+    int32_t d_max;     /* predictions are clamped to [0, d_max] tokens                        */
+} ps_model_info;
+
+/* Load a predictor (Sec. 3.3) from `path` (host string; file layout: 64-byte header, then the
+ * tensors in a fixed order, see the package's workload module) onto HIP device `device`.
+ * On success *out owns the device weights.  Errors: PS_EINVAL, PS_EIO, PS_EFORMAT, PS_ENOMEM,
+ * PS_EUNSUPPORTED (bf16 models need hidden % 256 == 0, ffn % 256 == 0 and head size 64),
+ * PS_EHIP. */
+int ps_model_load(const char* path /*host*/, int device, ps_model** out /*host*/);
+
+/* Release a model and its device memory.  NULL is allowed. */
+void ps_model_free(ps_model* model);
+
+/* Copy the model's shape into *out (host). */
+int ps_model_get_info(const ps_model* model, ps_model_info* out /*host*/);
+
+/* Bytes of device workspace ps_predict_load() needs for calls with at most `max_tokens` token
+ * slots (n_tokens below) and `max_req` requests.  0 on invalid arguments. */
+size_t ps_workspace_bytes(const ps_model* model, int64_t max_tokens, int32_t max_req);
+
+/* Predict the response length of n_req requests (Sec. 3.3).
+ *   token_ids   [n_tokens] int32; request r's text tokens start at offsets[r]; the caller puts
+ *               the [CLS] id first: the state of a request's first token is what is pooled.
+ *   offsets     [n_req + 1] int32, non-decreasing, offsets[n_req] == n_tokens.
+ *   lengths     NULL: packed layout, request r has offsets[r+1] - offsets[r] tokens.
+ *               else [n_req]: padded layout, request r has lengths[r] valid tokens at the start
+ *               of its span; the rest of the span is padding and takes no part in anything.
+ *   n_tokens    host scalar, number of token slots (= offsets[n_req]).
+ *   pred_f      [n_req] float, out: raw regression output (NaN for a faulty request).
+ *   pred_tokens [n_req] int32, out: pred_f rounded half-to-even and clamped to [0, d_max]
+ *               (-1 for a faulty request).
+ *   workspace   device scratch of at least ps_workspace_bytes(model, n_tokens, n_req) bytes,
+ *               256-byte aligned; contents are undefined before and after.
+ *   status      device ps_status or NULL; see above.  A request with a fault gets NaN / -1 and
+ *               does not disturb the others.
+ * Every request is processed with the model's n_soft learnable prompt rows appended after its
+ * text tokens.  n_req == 0 is allowed and does nothing. */
+int ps_predict_load(ps_model* model, const int32_t* token_ids, const int32_t* offsets,
+                    const int32_t* lengths, int32_t n_req, int64_t n_tokens,
+                    float* pred_f, int32_t* pred_tokens,
+                    void* workspace, size_t workspace_bytes, ps_status* status, void* hip_stream);
+
+/* Bytes of device workspace ps_anticipate() needs (partial curves of its workgroups).
+ * 0 on invalid arguments. */
+size_t ps_anticipate_workspace_bytes(int64_t n_req, int32_t n_inst, int32_t horizon);
+
+/* Fold n_req predictions into the per-instance future-load curves (Sec. 3.4.1: the look-ahead
+ * map is updated per request from its predicted response length).  Request r, assigned to
+ * instance_id[r] and arriving in one-second bucket arrival_bucket[r], decodes pred_tokens[r]
+ * tokens over `dur` consecutive buckets from its arrival bucket, spread as evenly as integers
+ * allow (the first pred % dur buckets take one more):
+ *     rate == NULL : dur = horizon - arrival          (spread to the end of the horizon)
+ *     otherwise    : dur = ceil(pred / rate[instance]) (rate[k] = tokens/s instance k decodes)
+ *   load      [n_inst * horizon] int32, row-major [instance][bucket]; ACCUMULATED into: the map
+ *             is persistent, the caller zeroes it to start afresh.
+ *   overflow  [n_inst] int64, accumulated: tokens that fall at or after `horizon`.  May be NULL
+ *             only if rate == NULL (nothing can overflow then).
+ *   workspace at least ps_anticipate_workspace_bytes(n_req, n_inst, horizon) bytes, 256-byte
+ *             aligned.
+ *   status    device ps_status or NULL.  Faulty records are skipped (PS_ST_BAD_RECORD).
+ * Integer arithmetic throughout: the result does not depend on record order and is bit-exact.
+ * Errors: PS_EINVAL, PS_EWORKSPACE, PS_EUNSUPPORTED (horizon too long for one row of the map
+ * to fit a compute unit's local memory), PS_EHIP.  n_req == 0 is allowed. */
+int ps_anticipate(const int32_t* pred_tokens, const int32_t* instance_id,
+                  const int32_t* arrival_bucket, const int32_t* rate,
+                  int64_t n_req, int32_t n_inst, int32_t horizon,
+                  int32_t* load, int64_t* overflow,
+                  void* workspace, size_t workspace_bytes, ps_status* status, void* hip_stream);
+
+/* Wait for `hip_stream` and copy a device ps_status to *out (host). */
+int ps_status_read(const ps_status* status /*device*/, void* hip_stream, ps_status* out /*host*/);
+
+/* Text for a PS_E* code (host string, static storage). */
+const char* ps_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PRESERVE_H */

@@ -1,0 +1,172 @@
+"""Thin ctypes binding over the C-ABI library (``include/preserve.h``), same names as the C calls.
+
+Argument marshalling only: tensors supply device pointers, ``torch.cuda.current_stream()`` the
+stream; every step of the path runs in the library's HIP kernels.  There is no fallback: if the
+library is missing or there is no GPU the calls raise."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpreserve.so")
+
+PS_OK = 0
+PS_ERRORS = {-1: "PS_EINVAL", -2: "PS_EIO", -3: "PS_EFORMAT", -4: "PS_ENOMEM", -5: "PS_EWORKSPACE",
+             -6: "PS_EUNSUPPORTED", -7: "PS_EHIP"}
+PS_ST_BAD_TOKEN, PS_ST_BAD_LENGTH, PS_ST_NAN, PS_ST_BAD_RECORD, PS_ST_RANGE = 0x01, 0x02, 0x04, 0x10, 0x20
+
+EXPORTS = ["ps_model_load", "ps_model_free", "ps_model_get_info", "ps_workspace_bytes", "ps_predict_load",
+           "ps_anticipate_workspace_bytes", "ps_anticipate", "ps_status_read", "ps_strerror"]
+
+
+class PsError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        super().__init__(f"{where}: {PS_ERRORS.get(code, code)}")
+        self.code = code
+
+
+class ps_model_info(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("layers", "hidden", "heads", "ffn", "vocab", "max_pos",
+                                              "n_soft", "head_hidden", "dtype", "d_max")]
+
+
+class ps_status(ctypes.Structure):
+    _fields_ = [("flags", ctypes.c_int32), ("reserved", ctypes.c_int32), ("first_bad", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load ``libpreserve.so`` (built in-tree by ``build.py``) and declare its entry points."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is not built; run paper_2504_03702_amd/build.py")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    lib.ps_model_load.restype = ctypes.c_int
+    lib.ps_model_load.argtypes = [ctypes.c_char_p, ctypes.c_int, ctypes.POINTER(vp)]
+    lib.ps_model_free.restype = None
+    lib.ps_model_free.argtypes = [vp]
+    lib.ps_model_get_info.restype = ctypes.c_int
+    lib.ps_model_get_info.argtypes = [vp, ctypes.POINTER(ps_model_info)]
+    lib.ps_workspace_bytes.restype = sz
+    lib.ps_workspace_bytes.argtypes = [vp, i64, i32]
+    lib.ps_predict_load.restype = ctypes.c_int
+    lib.ps_predict_load.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, sz, vp, vp]
+    lib.ps_anticipate_workspace_bytes.restype = sz
+    lib.ps_anticipate_workspace_bytes.argtypes = [i64, i32, i32]
+    lib.ps_anticipate.restype = ctypes.c_int
+    lib.ps_anticipate.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp, vp]
+    lib.ps_status_read.restype = ctypes.c_int
+    lib.ps_status_read.argtypes = [vp, vp, ctypes.POINTER(ps_status)]
+    lib.ps_strerror.restype = ctypes.c_char_p
+    lib.ps_strerror.argtypes = [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def _ptr(t: Optional[torch.Tensor], dtype: torch.dtype, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: need a contiguous {dtype} tensor on the GPU")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(code: int, where: str) -> None:
+    if code != PS_OK:
+        raise PsError(code, where)
+
+
+class Model:
+    """Owner of a ``ps_model*``."""
+
+    def __init__(self, handle: int, device: int):
+        self.handle, self.device = handle, device
+        info = ps_model_info()
+        _check(load_library().ps_model_get_info(handle, ctypes.byref(info)), "ps_model_get_info")
+        self.info = info
+
+    def close(self) -> None:
+        if self.handle:
+            load_library().ps_model_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def ps_model_load(path: str, device: int = 0) -> Model:
+    if not torch.cuda.is_available():
+        raise RuntimeError("ps_model_load needs a GPU")
+    out = ctypes.c_void_p()
+    _check(load_library().ps_model_load(os.fsencode(path), device, ctypes.byref(out)), "ps_model_load")
+    return Model(out.value, device)
+
+
+def ps_workspace_bytes(model: Model, max_tokens: int, max_req: int) -> int:
+    return int(load_library().ps_workspace_bytes(model.handle, max_tokens, max_req))
+
+
+def new_status(device="cuda") -> torch.Tensor:
+    """A zeroed device ps_status block (two int64 words)."""
+    return torch.zeros(2, dtype=torch.int64, device=device)
+
+
+def ps_status_read(status: torch.Tensor) -> Tuple[int, int]:
+    """(flags, first_bad) after waiting for the current stream."""
+    out = ps_status()
+    _check(load_library().ps_status_read(_ptr(status, torch.int64, "status"), _stream(), ctypes.byref(out)),
+           "ps_status_read")
+    return int(out.flags), int(out.first_bad)
+
+
+def ps_predict_load(model: Model, token_ids: torch.Tensor, offsets: torch.Tensor,
+                    lengths: Optional[torch.Tensor], pred_f: torch.Tensor, pred_tokens: torch.Tensor,
+                    workspace: torch.Tensor, status: Optional[torch.Tensor] = None) -> None:
+    n_req = offsets.numel() - 1
+    _check(load_library().ps_predict_load(
+        model.handle, _ptr(token_ids, torch.int32, "token_ids"), _ptr(offsets, torch.int32, "offsets"),
+        _ptr(lengths, torch.int32, "lengths"), n_req, token_ids.numel(),
+        _ptr(pred_f, torch.float32, "pred_f"), _ptr(pred_tokens, torch.int32, "pred_tokens"),
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+        _ptr(status, torch.int64, "status"), _stream()), "ps_predict_load")
+
+
+def ps_anticipate_workspace_bytes(n_req: int, n_inst: int, horizon: int) -> int:
+    return int(load_library().ps_anticipate_workspace_bytes(n_req, n_inst, horizon))
+
+
+def ps_anticipate(pred_tokens: torch.Tensor, instance_id: torch.Tensor, arrival_bucket: torch.Tensor,
+                  rate: Optional[torch.Tensor], n_inst: int, horizon: int, load: torch.Tensor,
+                  overflow: Optional[torch.Tensor], workspace: torch.Tensor,
+                  status: Optional[torch.Tensor] = None) -> None:
+    if load.numel() != n_inst * horizon or (overflow is not None and overflow.numel() != n_inst) or \
+            (rate is not None and rate.numel() != n_inst) or \
+            instance_id.numel() != pred_tokens.numel() or arrival_bucket.numel() != pred_tokens.numel():
+        raise ValueError("ps_anticipate: array sizes do not match n_req / n_inst / horizon")
+    _check(load_library().ps_anticipate(
+        _ptr(pred_tokens, torch.int32, "pred_tokens"), _ptr(instance_id, torch.int32, "instance_id"),
+        _ptr(arrival_bucket, torch.int32, "arrival_bucket"), _ptr(rate, torch.int32, "rate"),
+        pred_tokens.numel(), n_inst, horizon, _ptr(load, torch.int32, "load"),
+        _ptr(overflow, torch.int64, "overflow"), _ptr(workspace, torch.uint8, "workspace"),
+        workspace.numel(), _ptr(status, torch.int64, "status"), _stream()), "ps_anticipate")
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    """Uninitialised device scratch; torch's allocator hands out 512-byte aligned blocks."""
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)

@@ -1,0 +1,84 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "preserve.h"
+
+typedef uint16_t bf16_t;   // raw bf16 bit pattern
+
+#define PS_ROW_ALIGN   8     // every request starts at a multiple of this many activation rows
+#define PS_ROW_TILE    256   // activation buffers are padded to a multiple of this many rows
+#define PS_ATT_BQ      128   // query rows per attention workgroup (bf16 path)
+
+// Device weights of one encoder layer.  bf16 models: matrices are bf16, stored [out][in]
+// (the contraction index contiguous) for the MFMA kernels; fp32 models: float, [in][out].
+struct LayerWeights {
+    void *w_qkv, *w_o, *w_1, *w_2;
+    float *b_qkv, *b_o, *b_1, *b_2;
+    float *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+};
+
+struct ps_model {
+    ps_model_info info;
+    float ln_eps;
+    int device;
+    int lds_max;                 // largest LDS allocation of one workgroup on this device
+    void* blob;                  // the one device allocation everything below points into
+    size_t blob_bytes;
+    void *e_tok, *e_pos, *e_soft;     // embedding tables in the model's dtype, [rows][hidden]
+    float *lne_g, *lne_b;
+    std::vector<LayerWeights> layers;
+    float *w_h1t;                // [head_hidden][hidden]
+    float *b_h1, *w_h2;
+    float b_h2;
+};
+
+// Per-call bookkeeping the prep kernel writes at the start of the workspace.
+struct BatchMeta {
+    int32_t total_rows;          // activation rows in use (padded request starts included)
+    int32_t total_qtiles;        // attention query tiles over all requests
+    int32_t pad[2];
+};
+
+// Carved-up workspace of one ps_predict_load call.
+struct Workspace {
+    BatchMeta* meta;
+    int32_t *seq_len;            // [B]   rows of request r (text + learnable prompts), 0 if faulty
+    int32_t *row_start;          // [B+1] first activation row of request r
+    int32_t *qtile_start;        // [B+1] first attention query tile of request r
+    int32_t *bad_req;            // [B]   set when a request's text holds an invalid token id
+    void *x, *qkv, *vt, *att, *y, *x1, *g;
+    int64_t max_rows;            // rows every activation buffer holds (multiple of PS_ROW_TILE)
+    int64_t max_qtiles;
+    size_t bytes;
+};
+
+Workspace plan_workspace(const ps_model_info& info, int64_t n_tokens, int32_t n_req, void* base);
+
+// ---- launchers (each enqueues on `s`; all pointers are device pointers) -------------------
+void launch_prep(const ps_model* m, const int32_t* offsets, const int32_t* lengths, int32_t n_req,
+                 const Workspace& ws, ps_status* st, hipStream_t s);
+void launch_embed(const ps_model* m, const int32_t* token_ids, const int32_t* offsets, int32_t n_req,
+                  const Workspace& ws, ps_status* st, hipStream_t s);
+void launch_head(const ps_model* m, int32_t n_req, const Workspace& ws, const void* x_final,
+                 float* pred_f, int32_t* pred_tokens, ps_status* st, hipStream_t s);
+void run_encoder_f32(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s);
+void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s);
+
+// bf16 kernels
+enum GemmEpilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2, EPI_QKV = 3 };
+// C[rows, N] = A[rows, K] * W^T (+ epilogue); W is [N][K]; rows = *total_rows (device).
+void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias,
+                      const bf16_t* residual, bf16_t* C, bf16_t* vt, int64_t max_rows, int N, int K,
+                      int hidden, const int32_t* total_rows, hipStream_t s);
+void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s);
+void launch_layernorm_bf16(const bf16_t* in, bf16_t* out, const float* gamma, const float* beta,
+                           float eps, int hidden, int64_t max_rows, const int32_t* total_rows,
+                           hipStream_t s);
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

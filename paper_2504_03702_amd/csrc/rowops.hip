@@ -1,0 +1,230 @@
+// Per-call bookkeeping, embedding gather + LayerNorm, and the pooling + regression head.
+// These kernels are shared by the fp32 and the bf16 encoder paths.
+#include "device_util.h"
+#include "internal.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// prep: one workgroup turns (offsets, lengths) into the packed row layout of this call.
+// Request r occupies activation rows [row_start[r], row_start[r] + seq_len[r]); row_start is a
+// multiple of PS_ROW_ALIGN.  A request with an impossible length gets seq_len 0.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ offsets,
+                                                    const int32_t* __restrict__ lengths, int n_req,
+                                                    int n_soft, int max_pos, BatchMeta* meta,
+                                                    int32_t* seq_len, int32_t* row_start,
+                                                    int32_t* qtile_start, int32_t* bad_req,
+                                                    ps_status* st) {
+    __shared__ int s_rows[1024];
+    __shared__ int s_tiles[1024];
+    const int tid = threadIdx.x;
+    const int per = (n_req + 1023) / 1024;
+    const int r0 = tid * per;
+    const int r1 = min(r0 + per, n_req);
+    int rows = 0, tiles = 0;
+    for (int r = r0; r < r1; ++r) {
+        const int span = offsets[r + 1] - offsets[r];
+        const int len = lengths ? lengths[r] : span;
+        const bool bad = span < 0 || len < 1 || len > span || len > max_pos - n_soft;
+        const int S = bad ? 0 : len + n_soft;
+        if (bad) report_fault(st, PS_ST_BAD_LENGTH, r);
+        seq_len[r] = S;
+        bad_req[r] = 0;
+        rows += (S + PS_ROW_ALIGN - 1) / PS_ROW_ALIGN * PS_ROW_ALIGN;
+        tiles += (S + PS_ATT_BQ - 1) / PS_ATT_BQ;
+    }
+    s_rows[tid] = rows;
+    s_tiles[tid] = tiles;
+    __syncthreads();
+    // inclusive scan over the 1024 per-thread sums
+    for (int d = 1; d < 1024; d <<= 1) {
+        int a = 0, b = 0;
+        if (tid >= d) { a = s_rows[tid - d]; b = s_tiles[tid - d]; }
+        __syncthreads();
+        s_rows[tid] += a;
+        s_tiles[tid] += b;
+        __syncthreads();
+    }
+    int row = s_rows[tid] - rows, tile = s_tiles[tid] - tiles;
+    for (int r = r0; r < r1; ++r) {
+        row_start[r] = row;
+        qtile_start[r] = tile;
+        const int S = seq_len[r];
+        row += (S + PS_ROW_ALIGN - 1) / PS_ROW_ALIGN * PS_ROW_ALIGN;
+        tile += (S + PS_ATT_BQ - 1) / PS_ATT_BQ;
+    }
+    if (tid == 1023) {
+        row_start[n_req] = s_rows[1023];
+        qtile_start[n_req] = s_tiles[1023];
+        meta->total_rows = s_rows[1023];
+        meta->total_qtiles = s_tiles[1023];
+    }
+}
+
+template <typename T> __device__ inline float load_elem(const T* p, int64_t i);
+template <> __device__ inline float load_elem<float>(const float* p, int64_t i) { return p[i]; }
+template <> __device__ inline float load_elem<bf16_t>(const bf16_t* p, int64_t i) { return bf16_to_f32(p[i]); }
+template <typename T> __device__ inline void store_elem(T* p, int64_t i, float v);
+template <> __device__ inline void store_elem<float>(float* p, int64_t i, float v) { p[i] = v; }
+template <> __device__ inline void store_elem<bf16_t>(bf16_t* p, int64_t i, float v) { p[i] = f32_to_bf16(v); }
+
+// ------------------------------------------------------------------------------------------
+// embed: one wavefront per activation row.  Text rows gather a token embedding, the last n_soft
+// rows of a request take the learnable prompt vectors; both add the position embedding of the
+// row's index within its request and go through the embedding LayerNorm.  Rows that belong to
+// no request (alignment gaps, the tail up to the next row tile) are zero-filled so that every
+// row a later tile touches holds finite numbers.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ token_ids,
+                                                    const int32_t* __restrict__ offsets, int n_req,
+                                                    const T* __restrict__ e_tok, const T* __restrict__ e_pos,
+                                                    const T* __restrict__ e_soft,
+                                                    const float* __restrict__ gamma,
+                                                    const float* __restrict__ beta, float eps, int H,
+                                                    int vocab, int n_soft, const BatchMeta* meta,
+                                                    const int32_t* __restrict__ seq_len,
+                                                    const int32_t* __restrict__ row_start,
+                                                    int32_t* bad_req, T* __restrict__ x, ps_status* st) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int total = meta->total_rows;
+    const int64_t live = ((int64_t)total + PS_ROW_TILE - 1) / PS_ROW_TILE * PS_ROW_TILE;
+    if (row >= live) return;
+    T* out = x + row * H;
+    int r = -1, p = 0;
+    if (row < total) {
+        int lo = 0, hi = n_req - 1;          // largest r with row_start[r] <= row
+        while (lo < hi) {
+            int mid = (lo + hi + 1) >> 1;
+            if (row_start[mid] <= row) lo = mid; else hi = mid - 1;
+        }
+        r = lo;
+        p = (int)(row - row_start[r]);
+    }
+    const int S = r >= 0 ? seq_len[r] : 0;
+    if (r < 0 || p >= S) {
+        for (int i = lane; i < H; i += 64) store_elem<T>(out, i, 0.f);
+        return;
+    }
+    const int n_text = S - n_soft;
+    const T* src;
+    if (p < n_text) {
+        const int id = token_ids[offsets[r] + p];
+        if (id < 0 || id >= vocab) {
+            // faulty request: flagged here, its row zeroed; the head reports NaN / -1 for it
+            if (lane == 0) {
+                report_fault(st, PS_ST_BAD_TOKEN, r);
+                bad_req[r] = 1;
+            }
+            for (int i = lane; i < H; i += 64) store_elem<T>(out, i, 0.f);
+            return;
+        }
+        src = e_tok + (int64_t)id * H;
+    } else {
+        src = e_soft + (int64_t)(p - n_text) * H;
+    }
+    const T* pos = e_pos + (int64_t)p * H;
+    float sum = 0.f;
+    for (int i = lane; i < H; i += 64) sum += load_elem<T>(src, i) + load_elem<T>(pos, i);
+    const float mean = wave_sum(sum) / (float)H;
+    float sq = 0.f;
+    for (int i = lane; i < H; i += 64) {
+        const float dlt = load_elem<T>(src, i) + load_elem<T>(pos, i) - mean;
+        sq += dlt * dlt;
+    }
+    const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)H + eps);
+    for (int i = lane; i < H; i += 64) {
+        const float e = load_elem<T>(src, i) + load_elem<T>(pos, i);
+        store_elem<T>(out, i, (e - mean) * rstd * gamma[i] + beta[i]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// head: one workgroup per request.  c = final state of the request's first row; every wavefront
+// takes hidden units j = wave, wave + 4, ...: a 64-lane dot product of c with row j of W_h1^T
+// reduced across the wavefront, ReLU, times w_h2[j]; the four partial sums are added in a fixed
+// order.  pred_tokens = clamp(rint(y), 0, d_max) with rint rounding half to even.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, const int32_t* __restrict__ seq_len,
+                                                   const int32_t* __restrict__ row_start,
+                                                   const int32_t* __restrict__ bad_req, int H, int Hh,
+                                                   const float* __restrict__ w_h1t, const float* __restrict__ b_h1,
+                                                   const float* __restrict__ w_h2, float b_h2, int d_max,
+                                                   float* __restrict__ pred_f, int32_t* __restrict__ pred_tokens,
+                                                   ps_status* st) {
+    extern __shared__ float s_c[];           // [H] + 4 partial sums
+    const int r = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (seq_len[r] <= 0 || bad_req[r]) {
+        if (threadIdx.x == 0) {
+            pred_f[r] = __builtin_nanf("");
+            pred_tokens[r] = -1;
+        }
+        return;
+    }
+    const T* c = x + (int64_t)row_start[r] * H;
+    for (int i = threadIdx.x; i < H; i += 256) s_c[i] = load_elem<T>(c, i);
+    __syncthreads();
+    float acc = 0.f;
+    for (int j = wave; j < Hh; j += 4) {
+        const float* w = w_h1t + (int64_t)j * H;
+        float dot = 0.f;
+        for (int i = lane; i < H; i += 64) dot += s_c[i] * w[i];
+        dot = wave_sum(dot) + b_h1[j];
+        acc += fmaxf(dot, 0.f) * w_h2[j];
+    }
+    if (lane == 0) s_c[H + wave] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float y = ((s_c[H] + s_c[H + 1]) + (s_c[H + 2] + s_c[H + 3])) + b_h2;
+        pred_f[r] = y;
+        if (y != y) {
+            pred_tokens[r] = -1;
+            report_fault(st, PS_ST_NAN, r);
+        } else {
+            const float t = fminf(fmaxf(rintf(y), 0.f), (float)d_max);
+            pred_tokens[r] = (int32_t)t;
+        }
+    }
+}
+
+}  // namespace
+
+void launch_prep(const ps_model* m, const int32_t* offsets, const int32_t* lengths, int32_t n_req,
+                 const Workspace& ws, ps_status* st, hipStream_t s) {
+    hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(1024), 0, s, offsets, lengths, n_req, m->info.n_soft,
+                       m->info.max_pos, ws.meta, ws.seq_len, ws.row_start, ws.qtile_start, ws.bad_req, st);
+}
+
+void launch_embed(const ps_model* m, const int32_t* token_ids, const int32_t* offsets, int32_t n_req,
+                  const Workspace& ws, ps_status* st, hipStream_t s) {
+    const ps_model_info& f = m->info;
+    const unsigned blocks = (unsigned)(ws.max_rows / 4);
+    if (f.dtype == 1)
+        hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, token_ids, offsets, n_req,
+                           (const bf16_t*)m->e_tok, (const bf16_t*)m->e_pos, (const bf16_t*)m->e_soft,
+                           m->lne_g, m->lne_b, m->ln_eps, f.hidden, f.vocab, f.n_soft, ws.meta, ws.seq_len,
+                           ws.row_start, ws.bad_req, (bf16_t*)ws.x, st);
+    else
+        hipLaunchKernelGGL(embed_kernel<float>, dim3(blocks), dim3(256), 0, s, token_ids, offsets, n_req,
+                           (const float*)m->e_tok, (const float*)m->e_pos, (const float*)m->e_soft,
+                           m->lne_g, m->lne_b, m->ln_eps, f.hidden, f.vocab, f.n_soft, ws.meta, ws.seq_len,
+                           ws.row_start, ws.bad_req, (float*)ws.x, st);
+}
+
+void launch_head(const ps_model* m, int32_t n_req, const Workspace& ws, const void* x_final,
+                 float* pred_f, int32_t* pred_tokens, ps_status* st, hipStream_t s) {
+    const ps_model_info& f = m->info;
+    const size_t lds = sizeof(float) * (size_t)(f.hidden + 4);
+    if (f.dtype == 1)
+        hipLaunchKernelGGL(head_kernel<bf16_t>, dim3(n_req), dim3(256), lds, s, (const bf16_t*)x_final,
+                           ws.seq_len, ws.row_start, ws.bad_req, f.hidden, f.head_hidden, m->w_h1t, m->b_h1, m->w_h2,
+                           m->b_h2, f.d_max, pred_f, pred_tokens, st);
+    else
+        hipLaunchKernelGGL(head_kernel<float>, dim3(n_req), dim3(256), lds, s, (const float*)x_final,
+                           ws.seq_len, ws.row_start, ws.bad_req, f.hidden, f.head_hidden, m->w_h1t, m->b_h1, m->w_h2,
+                           m->b_h2, f.d_max, pred_f, pred_tokens, st);
+}

@@ -1,0 +1,97 @@
+"""GPU parity of ps_anticipate against the C oracle: bit-exact histograms on the same seeded
+inputs, through the C ABI."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from oracle import anticipator as oa
+from paper_2504_03702_amd import binding as ps
+from paper_2504_03702_amd import workloads as wl
+from tests.gpu_util import run_anticipate
+
+pytestmark = pytest.mark.gpu
+
+
+def check(inp, load0=None, ovf0=None):
+    got_load, got_ovf, flags, bad = run_anticipate(inp, load0, ovf0)
+    ref_load, ref_ovf, st, ref_bad = oa.anticipate(inp.pred_tokens, inp.instance_id, inp.arrival_bucket, inp.rate,
+                                                   inp.n_inst, inp.horizon, load=load0, overflow=ovf0)
+    assert np.array_equal(got_load, ref_load)
+    assert np.array_equal(got_ovf, ref_ovf)
+    assert bool(flags & ps.PS_ST_BAD_RECORD) == bool(st & 1)
+    if st & 1:
+        assert bad == ref_bad
+    return got_load, got_ovf, flags
+
+
+@pytest.mark.parametrize("kind,n", [("tiny", 16), ("tiny", 1), ("small", 64), ("medium", 1024),
+                                    ("production", 4096), ("production", 100_003), ("stream", 3_000_001)])
+def test_bit_exact(kind, n):
+    print(f"anticipator {kind} n={n}", flush=True)
+    inp = wl.make_anticipator_inputs(kind, seed=1, n=n)
+    load, ovf, flags = check(inp)
+    assert flags == 0
+    per_inst = np.bincount(inp.instance_id, weights=inp.pred_tokens, minlength=inp.n_inst).astype(np.int64)
+    assert np.array_equal(load.sum(axis=1, dtype=np.int64) + ovf, per_inst)
+
+
+def test_accumulates_into_existing_map():
+    inp = wl.make_anticipator_inputs("medium", seed=2, n=5000)
+    rng = np.random.default_rng(0)
+    load0 = rng.integers(-1000, 1000, (inp.n_inst, inp.horizon)).astype(np.int32)
+    ovf0 = rng.integers(0, 10**12, inp.n_inst).astype(np.int64)
+    check(inp, load0, ovf0)
+
+
+def test_odd_shapes_and_many_groups():
+    # rows that do not divide into groups evenly, a horizon that is no multiple of anything
+    rng = np.random.default_rng(3)
+    for n_inst, horizon, n in [(1, 1, 10), (3, 7, 100), (301, 1021, 20000), (37, 9000, 5000), (1000, 64, 30000)]:
+        print(f"anticipator odd K={n_inst} Hz={horizon} n={n}", flush=True)
+        inp = wl.AnticipatorInputs(rng.integers(0, 5000, n, dtype=np.int32), rng.integers(0, n_inst, n, dtype=np.int32),
+                                   rng.integers(0, horizon, n, dtype=np.int32),
+                                   rng.integers(1, 200, n_inst, dtype=np.int32), n_inst, horizon)
+        check(inp)
+        check(dataclasses.replace(inp, rate=None))
+
+
+def test_bad_records_are_skipped_and_flagged():
+    inp = wl.make_anticipator_inputs("small", seed=4, n=500)
+    inp.pred_tokens[[17, 400]] = [-5, 1 << 25]
+    inp.instance_id[[99, 250]] = [inp.n_inst, -1]
+    inp.arrival_bucket[[33, 480]] = [inp.horizon, -2]
+    ok = np.ones(500, bool)
+    ok[[17, 400, 99, 250, 33, 480]] = False
+    got_load, got_ovf, flags, bad = run_anticipate(inp)
+    assert flags & ps.PS_ST_BAD_RECORD and bad == 17
+    # the oracle has no upper limit on pred_tokens, so compare on the records both accept
+    clean = wl.AnticipatorInputs(inp.pred_tokens[ok], inp.instance_id[ok], inp.arrival_bucket[ok], inp.rate,
+                                 inp.n_inst, inp.horizon)
+    ref_load, ref_ovf, st, _ = oa.anticipate(clean.pred_tokens, clean.instance_id, clean.arrival_bucket, clean.rate,
+                                             clean.n_inst, clean.horizon)
+    assert st == 0 and np.array_equal(got_load, ref_load) and np.array_equal(got_ovf, ref_ovf)
+    bad_rate = dataclasses.replace(clean, rate=np.where(np.arange(inp.n_inst) == 2, 0, inp.rate).astype(np.int32))
+    check(bad_rate)
+
+
+def test_int32_range_is_flagged():
+    inp = wl.AnticipatorInputs(np.array([8], np.int32), np.array([0], np.int32), np.array([0], np.int32), None, 1, 4)
+    load0 = np.full((1, 4), 2**31 - 2, np.int32)
+    got_load, _, flags, _ = run_anticipate(inp, load0)
+    assert flags & ps.PS_ST_RANGE
+    assert got_load[0].tolist() == [-(2**31)] * 4
+
+
+def test_host_side_argument_errors():
+    import torch
+    dev = "cuda:0"
+    z = torch.zeros(4, dtype=torch.int32, device=dev)
+    load = torch.zeros(8, dtype=torch.int32, device=dev)
+    ws = ps.alloc_workspace(ps.ps_anticipate_workspace_bytes(4, 2, 4), dev)
+    with pytest.raises(ps.PsError) as e:      # a rate needs an overflow array
+        ps.ps_anticipate(z, z, z, torch.ones(2, dtype=torch.int32, device=dev), 2, 4, load, None, ws)
+    assert e.value.code == -1
+    with pytest.raises(ps.PsError) as e:      # workspace too small
+        ps.ps_anticipate(z, z, z, None, 2, 4, load, None, ws[:256].contiguous()[:16])
+    assert e.value.code == -5
