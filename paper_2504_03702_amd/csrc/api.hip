@@ -100,7 +100,7 @@ Workspace plan_workspace(const ps_model_info& info, int64_t n_tokens, int32_t n_
     ws.bad_req = (int32_t*)take(sizeof(int32_t) * (size_t)(n_req + 1));
     ws.x = take(es * rows * H);
     ws.qkv = take(es * rows * 3 * H);
-    ws.vt = info.dtype == 1 ? take(es * rows * H) : nullptr;
+    ws.vt = info.dtype == 1 ? take(es * rows * H + 1024) : nullptr;   // + slack: the last key tile may read past a row end
     ws.att = take(es * rows * H);
     ws.y = take(es * rows * H);
     ws.x1 = take(es * rows * H);
@@ -157,7 +157,7 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
                              (uint64_t)H * Hh + 2 * Hh + 1;
     if (raw.size() != kHeaderBytes + n_elems * fe) return PS_EFORMAT;
     const int d = info.hidden / info.heads;
-    if (info.dtype == 1 && (H % 256 != 0 || F % 256 != 0 || d != 64)) return PS_EUNSUPPORTED;
+    if (info.dtype == 1 && (H % 256 != 0 || H > 2048 || F % 256 != 0 || d != 64)) return PS_EUNSUPPORTED;
     if (info.dtype == 0 && (d > 256 || H > 8192 || (P + d) * 16 > 60000 || 3 * H / 64 > 65535)) return PS_EUNSUPPORTED;
 
     if (hipSetDevice(device) != hipSuccess) return PS_EHIP;

@@ -1,0 +1,225 @@
+// Varlen multi-head self-attention on the gfx950 matrix cores (head size 64, bf16 in, fp32
+// softmax statistics and accumulation).
+//
+// One workgroup handles 128 consecutive query rows of one request and one head; each of its four
+// wavefronts owns 32 of them.  Keys and values are streamed in tiles of 64 keys through LDS
+// (global_load_lds, double buffered) and shared by the four wavefronts.  Everything is computed
+// transposed so that a query is a column, i.e. a lane:
+//     S^T[key, q] = K[key, :] . Q[q, :]          (v_mfma_f32_32x32x16_bf16, A = K tile, B = Q^T)
+//     O^T[d, q]  += V^T[d, key] . P^T[key, q]    (A = V^T tile, B = P^T taken from the S^T registers)
+// so the running maximum, the running sum and the rescale factor of a query are per-lane scalars
+// and the softmax needs one cross-lane exchange per tile (between the two half-wavefronts that
+// hold different keys of the same query).  The accumulator layout of S^T is, up to the order of the
+// contraction index (which A and B only have to agree on), the B-operand layout of the second
+// product, so P never leaves registers.  The 1/sqrt(64) scale is folded into the query projection
+// when the model is loaded.  The value tile is read keys-contiguous from the transposed copy Vt
+// that the QKV projection's epilogue writes.
+//
+// Keys beyond the request's length in the last tile are excluded: their scores are set to -inf
+// before the maximum and their value entries to zero (they may hold anything).
+#include "device_util.h"
+#include "internal.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define GLOBAL_AS __attribute__((address_space(1)))
+#define LDS_AS __attribute__((address_space(3)))
+
+__device__ __forceinline__ int swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+
+union Frag8 {
+    bf16x8 v;
+    uint32_t u[4];
+    uint2 h[2];
+};
+
+constexpr int BK = 64;                 // keys per tile
+constexpr int TILE_BYTES = BK * 128;   // K tile [64 keys][64 d] or V^T tile [64 d][64 keys]
+constexpr float LOG2E = 1.4426950408889634f;
+
+__global__ __launch_bounds__(256) void attention_bf16_kernel(
+    const bf16_t* __restrict__ qk,      // [rows][2H]: query columns then key columns
+    const bf16_t* __restrict__ vt,      // [H][vt_ld]: value features x rows
+    bf16_t* __restrict__ out,           // [rows][H]
+    int H, int64_t vt_ld, int n_req, const BatchMeta* __restrict__ meta,
+    const int32_t* __restrict__ seq_len, const int32_t* __restrict__ row_start,
+    const int32_t* __restrict__ qtile_start) {
+    __shared__ __align__(1024) unsigned char smem[2 * 2 * TILE_BYTES];   // 2 stages x (K, V^T)
+
+    const int qt = blockIdx.x, head = blockIdx.y;
+    if (qt >= meta->total_qtiles) return;
+    int lo = 0, hi = n_req - 1;          // request of this query tile: largest r with qtile_start[r] <= qt
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (qtile_start[mid] <= qt) lo = mid; else hi = mid - 1;
+    }
+    const int S = seq_len[lo];
+    const int base = row_start[lo];
+    const int q0 = (qt - qtile_start[lo]) * PS_ATT_BQ;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    const int last_row = base + S - 1;
+    const int64_t ld_qk = 2 * (int64_t)H;
+
+    // ---- this wavefront's queries: B operand fragments, one per 16-deep slice of the head -------
+    const int wq0 = q0 + 32 * wave;
+    const bool active = wq0 < S;                              // wave-uniform
+    const int my_q = base + wq0 + col;
+    const bf16_t* qrow = qk + (int64_t)min(my_q, last_row) * ld_qk + head * 64;
+    bf16x8 qf[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) qf[ks] = *(const bf16x8*)(qrow + (2 * ks + half) * 8);
+
+    // ---- DMA addressing: 2 instructions per wavefront per tile for K, 2 for V^T ------------------
+    const int drow = lane >> 3;                               // row within an 8-row group
+    auto dma_tile = [&](int stage, int k0) {
+        unsigned char* sK = smem + stage * 2 * TILE_BYTES;
+        unsigned char* sV = sK + TILE_BYTES;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int grp = j * 4 + wave;
+            const int r = grp * 8 + drow;                     // key row (K tile) / feature row (V^T tile)
+            const int c = (lane & 7) ^ swz(r);
+            const bf16_t* gk = qk + (int64_t)min(base + k0 + r, last_row) * ld_qk + H + head * 64 + c * 8;
+            __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)gk, (LDS_AS void*)(sK + grp * 1024), 16, 0, 0);
+            const bf16_t* gv = vt + (int64_t)(head * 64 + r) * vt_ld + base + k0 + c * 8;
+            __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)gv, (LDS_AS void*)(sV + grp * 1024), 16, 0, 0);
+        }
+    };
+
+    // ---- LDS fragment offsets ---------------------------------------------------------------------
+    int koff[4];                                              // K tile: row col, chunk 2ks + half
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) koff[ks] = col * 128 + (((2 * ks + half) ^ swz(col)) * 16);
+    int voff[8];                                              // V^T tile: row col, chunk c, 8-byte half
+#pragma unroll
+    for (int c = 0; c < 8; ++c) voff[c] = col * 128 + ((c ^ swz(col)) * 16) + 8 * half;
+
+    f32x16 o[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[i][e] = 0.f;
+    float m_run = -INFINITY;      // running maximum of this lane's query (same in both half-waves)
+    float l_run = 0.f;            // running sum over the keys this half-wave holds
+
+    const int nkt = (S + BK - 1) / BK;
+    dma_tile(0, 0);
+    for (int kt = 0; kt < nkt; ++kt) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();                                      // tile kt landed; tile kt-1 no longer read
+        if (kt + 1 < nkt) dma_tile((kt + 1) & 1, (kt + 1) * BK);
+        if (!active) continue;
+        const unsigned char* sK = smem + (kt & 1) * 2 * TILE_BYTES;
+        const unsigned char* sV = sK + TILE_BYTES;
+        const int k0 = kt * BK;
+
+        // S^T = K Q^T for the two 32-key blocks
+        f32x16 s[2];
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[b][e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const bf16x8 kf = *(const bf16x8*)(sK + b * 4096 + koff[ks]);
+                s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[b], 0, 0, 0);
+            }
+        }
+        // element e of block b is key k0 + 32 b + 8 (e / 4) + 4 half + e % 4
+        const bool partial = k0 + BK > S;                     // uniform
+        if (partial) {
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int key = k0 + 32 * b + 8 * (e >> 2) + 4 * half + (e & 3);
+                    if (key >= S) s[b][e] = -INFINITY;
+                }
+        }
+        float mx = s[0][0];
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[b][e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);                 // finite: every tile holds a valid key
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * LOG2E);
+        const float mb = m_new * LOG2E;
+        m_run = m_new;
+        float psum = 0.f;
+        Frag8 pf[2][2];                                       // P^T fragments: [key block][16-key step]
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[b][8 * j + 2 * t], LOG2E, -mb));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[b][8 * j + 2 * t + 1], LOG2E, -mb));
+                    psum += p0 + p1;
+                    pf[b][j].u[t] = pack_bf16x2(p0, p1);
+                }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
+
+        // O^T += V^T P^T.  Step (b, j) contracts keys 32 b + 16 j + {4 half + 0..3, 8 + 4 half + 0..3},
+        // the keys the P fragment holds, so the value fragment is two 8-byte reads.
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int c0 = 4 * b + 2 * j;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    Frag8 vf;
+                    vf.h[0] = *(const uint2*)(sV + i * 4096 + voff[c0]);
+                    vf.h[1] = *(const uint2*)(sV + i * 4096 + voff[c0 + 1]);
+                    if (partial) {
+                        // zero the value entries of keys beyond the request
+                        const int key = k0 + 32 * b + 16 * j + 4 * half;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const int kk = key + (t >> 1) * 8 + (t & 1) * 2;     // keys kk, kk + 1
+                            uint32_t w = vf.u[t];
+                            if (kk >= S) w = 0; else if (kk + 1 >= S) w &= 0xffffu;
+                            vf.u[t] = w;
+                        }
+                    }
+                    o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[b][j].v, o[i], 0, 0, 0);
+                }
+            }
+    }
+    if (!active) return;
+
+    // ---- normalise and store: element e of block i is feature 32 i + 8 (e / 4) + 4 half + e % 4 -----
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = 1.0f / l_tot;
+    if (wq0 + col < S) {
+        bf16_t* orow = out + (int64_t)my_q * H + head * 64;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const uint2 p = make_uint2(pack_bf16x2(o[i][4 * e4] * inv, o[i][4 * e4 + 1] * inv),
+                                           pack_bf16x2(o[i][4 * e4 + 2] * inv, o[i][4 * e4 + 3] * inv));
+                *(uint2*)(orow + 32 * i + 8 * e4 + 4 * half) = p;
+            }
+    }
+}
+
+}  // namespace
+
+void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s) {
+    const dim3 grid((unsigned)ws.max_qtiles, (unsigned)m->info.heads);
+    hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16_t*)ws.qkv, (const bf16_t*)ws.vt,
+                       (bf16_t*)ws.att, m->info.hidden, ws.max_rows, n_req, ws.meta, ws.seq_len, ws.row_start,
+                       ws.qtile_start);
+}

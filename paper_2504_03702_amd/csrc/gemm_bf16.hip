@@ -1,0 +1,248 @@
+// bf16 GEMM on the gfx950 matrix cores with fused epilogues.
+//
+//   C[m, n] = sum_k A[m, k] * W[n, k]   (A: activations [rows][K], W: weights [N][K], both bf16,
+//                                        contraction index contiguous; fp32 accumulation)
+//   epilogue: + bias[n], then one of: store | erf-GELU, store | + residual[m, n], store |
+//             QKV split (query and key columns to [rows][2H], value columns transposed to
+//             Vt[H][max_rows] so the attention kernel reads keys-contiguous value tiles).
+//
+// One workgroup computes a BM x BN tile.  Per 64-deep k slice the A and W sub-tiles are brought
+// straight from global memory into LDS (global_load_lds, 16 bytes per lane, no register staging),
+// double buffered; each wavefront then reads 32 x 16 fragments with ds_read_b128 and issues
+// v_mfma_f32_32x32x16_bf16.  LDS rows are 128 bytes (64 bf16); the 16-byte chunks of a row are
+// XOR-swizzled with the row index so that the 8 or 16 rows one ds_read_b128 phase touches fall in
+// different banks.  The swizzle is applied on the global side of the DMA (each lane picks which
+// chunk it fetches), since the LDS side of a DMA is always lane-linear.
+//
+// The number of rows is only known on the device (padded inputs are compacted), so the grid is
+// sized for the host's upper bound and workgroups beyond the live tiles leave at once.  Workgroups
+// are dealt to the 8 XCDs round-robin by the hardware; the tile index is remapped so that each XCD
+// works on a contiguous run of tiles (n fastest), keeping an A row panel hot in that XCD's L2.
+#include "device_util.h"
+#include "internal.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define GLOBAL_AS __attribute__((address_space(1)))
+#define LDS_AS __attribute__((address_space(3)))
+
+// chunk swizzle of LDS row `r` (see the header comment); depends on r mod 16 only
+__device__ __forceinline__ int swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+
+__device__ __forceinline__ float gelu_erf(float v) {
+    return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f));
+}
+
+template <int BM, int BN, int WM, int WN>
+struct Tile {
+    static constexpr int NW = WM * WN;               // wavefronts per workgroup
+    static constexpr int THREADS = NW * 64;
+    static constexpr int TM = BM / WM / 32;          // 32 x 32 accumulator tiles per wavefront
+    static constexpr int TN = BN / WN / 32;
+    static constexpr int A_BYTES = BM * 128;         // one 64-deep slice
+    static constexpr int B_BYTES = BN * 128;
+    static_assert(NW % 2 == 0 && BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile / wave split");
+};
+
+// Bring ROWS x 64 bf16 (rows `ld` elements apart in global memory) into an LDS slice.  `base` is
+// the wave-uniform address of the slice's first row, `lane_off` this lane's byte offset inside the
+// first 8 * NW rows; the uniform part stays in scalar registers so each DMA costs one VGPR.
+template <int ROWS, int NW>
+__device__ __forceinline__ void dma_slice(const unsigned char* base, unsigned lane_off, int64_t ld_bytes,
+                                          unsigned char* lds, int wave) {
+#pragma unroll
+    for (int j = 0; j < ROWS / 8 / NW; ++j) {
+        const uint64_t u = (uint64_t)(base + (int64_t)j * (NW * 8) * ld_bytes);
+        const unsigned char* ub = (const unsigned char*)(((uint64_t)__builtin_amdgcn_readfirstlane((unsigned)(u >> 32)) << 32) |
+                                                        __builtin_amdgcn_readfirstlane((unsigned)u));
+        const unsigned char* g = ub + lane_off;
+        __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)g, (LDS_AS void*)(lds + (j * NW + wave) * 1024),
+                                         16, 0, 0);
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int EPI>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
+    const bf16_t* __restrict__ residual, bf16_t* __restrict__ C, bf16_t* __restrict__ Vt, int64_t vt_ld,
+    int N, int K, int hidden, const int32_t* __restrict__ total_rows) {
+    using T = Tile<BM, BN, WM, WN>;
+    // two stages, each an A slice followed by a W slice
+    __shared__ __align__(1024) unsigned char smem[2 * (T::A_BYTES + T::B_BYTES)];
+    constexpr int STAGE = T::A_BYTES + T::B_BYTES;
+
+    // ---- which tile ------------------------------------------------------------------------
+    const int rows = *total_rows;
+    const int n_tiles = N / BN;
+    const int m_tiles = (rows + BM - 1) / BM;
+    const int tiles = m_tiles * n_tiles;
+    const int per_xcd = (tiles + 7) >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int tile = xcd * per_xcd + slot;
+    if (slot >= per_xcd || tile >= tiles) return;
+    const int m0 = (tile / n_tiles) * BM, n0 = (tile % n_tiles) * BN;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    // ---- DMA sources: lane i of a wavefront fetches chunk (i%8)^swz of row i/8 of its group ----
+    const int dma_row = wave * 8 + (lane >> 3);
+    const int dma_chunk = (lane & 7) ^ swz(dma_row);
+    const unsigned lane_off = (unsigned)(dma_row * K + dma_chunk * 8) * 2u;
+    const int64_t ld_bytes = (int64_t)K * 2;
+    const unsigned char* ga = (const unsigned char*)(A + (int64_t)m0 * K);      // wave-uniform
+    const unsigned char* gw = (const unsigned char*)(W + (int64_t)n0 * K);
+
+    // ---- fragment addresses: row (lane%32) of a 32-row tile, chunks 2*ks + lane/32 ----------
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int a_off = (wm * (BM / WM) + frow) * 128;
+    const int b_off = (wn * (BN / WN) + frow) * 128;
+    int koff[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) koff[ks] = ((2 * ks + fhalf) ^ swz(frow)) * 16;
+
+    f32x16 acc[T::TM][T::TN];
+#pragma unroll
+    for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < T::TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // Fragment double buffer: while the MFMAs of k-step s run, the ds_reads of step s+1 are in
+    // flight.  Schedule per 64-deep slice kt (stage kt&1 holds it):
+    //   steps 0..2 : read fragments of the next step of this slice | MFMAs of the current step
+    //   then       : wait for this wavefront's DMA of slice kt+1, workgroup barrier (now every
+    //                wavefront has read its last fragments of slice kt and slice kt+1 is visible),
+    //                start the DMA of slice kt+2 into the stage slice kt occupied
+    //   step 3     : read step-0 fragments of slice kt+1 | MFMAs of step 3
+    bf16x8 fa0[T::TM], fb0[T::TN], fa1[T::TM], fb1[T::TN];
+    auto read_frags = [&](bf16x8* fa, bf16x8* fb, const unsigned char* stage, int ks) {
+        const unsigned char* sA = stage + a_off + koff[ks];
+        const unsigned char* sB = stage + T::A_BYTES + b_off + koff[ks];
+#pragma unroll
+        for (int i = 0; i < T::TM; ++i) fa[i] = *(const bf16x8*)(sA + i * 4096);
+#pragma unroll
+        for (int j = 0; j < T::TN; ++j) fb[j] = *(const bf16x8*)(sB + j * 4096);
+    };
+    auto mfma_step = [&](const bf16x8* fa, const bf16x8* fb) {
+#pragma unroll
+        for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+            for (int j = 0; j < T::TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    };
+    // interleave: one LDS read, then its share of the MFMAs
+    auto interleave = [&]() {
+#pragma unroll
+        for (int r = 0; r < T::TM + T::TN; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                   // DS read
+            __builtin_amdgcn_sched_group_barrier(0x008, T::TM * T::TN / (T::TM + T::TN), 0);     // MFMA
+        }
+    };
+
+    const int nk = K / 64;
+    dma_slice<BM, T::NW>(ga, lane_off, ld_bytes, smem, wave);
+    dma_slice<BN, T::NW>(gw, lane_off, ld_bytes, smem + T::A_BYTES, wave);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (nk > 1) {
+        dma_slice<BM, T::NW>(ga + 128, lane_off, ld_bytes, smem + STAGE, wave);
+        dma_slice<BN, T::NW>(gw + 128, lane_off, ld_bytes, smem + STAGE + T::A_BYTES, wave);
+    }
+    read_frags(fa0, fb0, smem, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+        unsigned char* cur = smem + (kt & 1) * STAGE;
+        unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
+        read_frags(fa1, fb1, cur, 1);
+        mfma_step(fa0, fb0);
+        interleave();
+        read_frags(fa0, fb0, cur, 2);
+        mfma_step(fa1, fb1);
+        interleave();
+        read_frags(fa1, fb1, cur, 3);
+        mfma_step(fa0, fb0);
+        interleave();
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (kt + 2 < nk) {
+            dma_slice<BM, T::NW>(ga + (kt + 2) * 128, lane_off, ld_bytes, cur, wave);
+            dma_slice<BN, T::NW>(gw + (kt + 2) * 128, lane_off, ld_bytes, cur + T::A_BYTES, wave);
+        }
+        if (kt + 1 < nk) read_frags(fa0, fb0, nxt, 0);
+        mfma_step(fa1, fb1);
+        interleave();
+    }
+
+    // ---- epilogue: accumulator element e of tile (i, j) is C[row, col] with
+    //      row = 32 i + 8 (e / 4) + 4 (lane / 32) + e % 4,  col = 32 j + lane % 32 -------------
+    const int row_base = m0 + wm * (BM / WM) + 4 * fhalf;
+    const int col_base = n0 + wn * (BN / WN) + frow;
+#pragma unroll
+    for (int j = 0; j < T::TN; ++j) {
+        const int col = col_base + 32 * j;
+        const float bv = bias[col];
+#pragma unroll
+        for (int i = 0; i < T::TM; ++i) {
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const int row = row_base + 32 * i + 8 * e4;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * e4 + e] + bv;
+                if (EPI == EPI_BIAS_GELU) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
+                }
+                if (EPI == EPI_BIAS_RESIDUAL) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] += bf16_to_f32(residual[(int64_t)(row + e) * N + col]);
+                }
+                if (EPI == EPI_QKV) {
+                    if (col >= 2 * hidden) {
+                        // value columns: 4 consecutive tokens of one feature row of Vt
+                        uint2 p = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+                        *(uint2*)(Vt + (int64_t)(col - 2 * hidden) * vt_ld + row) = p;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) C[(int64_t)(row + e) * (2 * hidden) + col] = f32_to_bf16(v[e]);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) C[(int64_t)(row + e) * N + col] = f32_to_bf16(v[e]);
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN>
+void launch_cfg(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias, const bf16_t* residual,
+                bf16_t* C, bf16_t* vt, int64_t max_rows, int N, int K, int hidden, const int32_t* total_rows,
+                hipStream_t s) {
+    const int64_t tiles = (max_rows + BM - 1) / BM * (N / BN);
+    const dim3 grid((unsigned)((tiles + 7) / 8 * 8)), block(WM * WN * 64);
+#define PS_LAUNCH(E)                                                                                       \
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, E>), grid, block, 0, s, A, W, bias, residual, C, vt, \
+                       max_rows, N, K, hidden, total_rows)
+    switch (epi) {
+        case EPI_BIAS: PS_LAUNCH(EPI_BIAS); break;
+        case EPI_BIAS_GELU: PS_LAUNCH(EPI_BIAS_GELU); break;
+        case EPI_BIAS_RESIDUAL: PS_LAUNCH(EPI_BIAS_RESIDUAL); break;
+        case EPI_QKV: PS_LAUNCH(EPI_QKV); break;
+    }
+#undef PS_LAUNCH
+}
+
+}  // namespace
+
+// Requirements (checked when the model is loaded): N % 256 == 0, K % 64 == 0; every buffer holds
+// max_rows rows with max_rows % 256 == 0, so whole tiles are always in bounds.
+void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias,
+                      const bf16_t* residual, bf16_t* C, bf16_t* vt, int64_t max_rows, int N, int K,
+                      int hidden, const int32_t* total_rows, hipStream_t s) {
+    launch_cfg<256, 256, 2, 2>(epi, A, W, bias, residual, C, vt, max_rows, N, K, hidden, total_rows, s);
+}

@@ -36,7 +36,7 @@ def test_tiny_config(tmp_models, seed, n_req):
     assert flags == 0
     assert rel_err(got_f, ref_f).max() < TOL_FP32
     check_tokens(got_f, got_t, ref_t, TINY.d_max)
-    assert np.ptp(ref_f) > 1.0
+    assert n_req == 1 or np.ptp(ref_f) > 1.0
 
 
 def test_padded_layout_equals_packed(tmp_models):
