@@ -102,7 +102,14 @@ Workspace plan_workspace(const ps_model_info& info, int64_t n_tokens, int32_t n_
     ws.qkv = take(es * rows * 3 * H);
     ws.vt = info.dtype == 1 ? take(es * rows * H + 1024) : nullptr;   // + slack: the last key tile may read past a row end
     ws.att = take(es * rows * H);
-    ws.y = take(es * rows * H);
+    if (info.dtype == 1) {
+        ws.ya = (float*)take(4 * rows * H);
+        ws.yb = (float*)take(4 * rows * H);
+        ws.sa = (float2*)take(8 * rows);
+        ws.sb = (float2*)take(8 * rows);
+    } else {
+        ws.y = take(es * rows * H);
+    }
     ws.x1 = take(es * rows * H);
     ws.g = take(es * rows * F);
     ws.bytes = off;
@@ -334,7 +341,7 @@ extern "C" int ps_predict_load(ps_model* m, const int32_t* token_ids, const int3
     launch_embed(m, token_ids, offsets, n_req, ws, status, s);
     if (m->info.dtype == 1) run_encoder_bf16(m, n_req, ws, s);
     else run_encoder_f32(m, n_req, ws, s);
-    launch_head(m, n_req, ws, ws.x, pred_f, pred_tokens, status, s);
+    launch_head(m, n_req, ws, pred_f, pred_tokens, status, s);
     return hipGetLastError() == hipSuccess ? PS_OK : PS_EHIP;
 }
 

@@ -5,11 +5,13 @@
 
 namespace {
 
-// LayerNorm of one row per wavefront (biased variance).  A row is H = 256 * NCH bf16; lane l holds
-// the 4-element chunks l, l + 64, ... so every load and store of a wavefront is one contiguous
-// 512-byte run.  Statistics in fp32 from the values held in registers; in == out is allowed.
+// LayerNorm of one row of fp32 sums per wavefront (biased variance): writes the bf16 row the
+// next GEMM reads and the row's (mean, 1/std), from which later epilogues recompute the fp32
+// LayerNorm output.  A row is H = 256 * NCH floats; lane l holds the 4-element chunks l, l + 64, ...
+// so every load and store of a wavefront is one contiguous run.
 template <int NCH>
-__global__ __launch_bounds__(256) void layernorm_bf16_kernel(const bf16_t* __restrict__ in, bf16_t* __restrict__ out,
+__global__ __launch_bounds__(256) void layernorm_bf16_kernel(const float* __restrict__ y, bf16_t* __restrict__ x,
+                                                             float2* __restrict__ stats,
                                                              const float* __restrict__ gamma,
                                                              const float* __restrict__ beta, float eps,
                                                              const int32_t* __restrict__ total_rows) {
@@ -17,44 +19,40 @@ __global__ __launch_bounds__(256) void layernorm_bf16_kernel(const bf16_t* __res
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= *total_rows) return;
-    const uint2* src = (const uint2*)(in + row * H);
-    float x[NCH][4];
+    const float4* src = (const float4*)(y + row * H);
+    float4 v[NCH];
     float sum = 0.f;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        const uint2 v = src[lane + 64 * c];
-        x[c][0] = __uint_as_float(v.x << 16);
-        x[c][1] = __uint_as_float(v.x & 0xffff0000u);
-        x[c][2] = __uint_as_float(v.y << 16);
-        x[c][3] = __uint_as_float(v.y & 0xffff0000u);
-        sum += (x[c][0] + x[c][1]) + (x[c][2] + x[c][3]);
+        v[c] = src[lane + 64 * c];
+        sum += (v[c].x + v[c].y) + (v[c].z + v[c].w);
     }
     const float mean = wave_sum(sum) * (1.0f / H);
     float sq = 0.f;
 #pragma unroll
-    for (int c = 0; c < NCH; ++c)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            x[c][e] -= mean;
-            sq = fmaf(x[c][e], x[c][e], sq);
-        }
+    for (int c = 0; c < NCH; ++c) {
+        v[c].x -= mean; v[c].y -= mean; v[c].z -= mean; v[c].w -= mean;
+        sq = fmaf(v[c].x, v[c].x, sq); sq = fmaf(v[c].y, v[c].y, sq);
+        sq = fmaf(v[c].z, v[c].z, sq); sq = fmaf(v[c].w, v[c].w, sq);
+    }
     const float rstd = 1.0f / sqrtf(wave_sum(sq) * (1.0f / H) + eps);
-    uint2* dst = (uint2*)(out + row * H);
+    if (lane == 0) stats[row] = make_float2(mean, rstd);
+    uint2* dst = (uint2*)(x + row * H);
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const float4 g = ((const float4*)gamma)[lane + 64 * c];
         const float4 b = ((const float4*)beta)[lane + 64 * c];
-        dst[lane + 64 * c] = make_uint2(pack_bf16x2(x[c][0] * rstd * g.x + b.x, x[c][1] * rstd * g.y + b.y),
-                                        pack_bf16x2(x[c][2] * rstd * g.z + b.z, x[c][3] * rstd * g.w + b.w));
+        dst[lane + 64 * c] = make_uint2(pack_bf16x2(v[c].x * rstd * g.x + b.x, v[c].y * rstd * g.y + b.y),
+                                        pack_bf16x2(v[c].z * rstd * g.z + b.z, v[c].w * rstd * g.w + b.w));
     }
 }
 
 }  // namespace
 
-void launch_layernorm_bf16(const bf16_t* in, bf16_t* out, const float* gamma, const float* beta, float eps,
-                           int hidden, int64_t max_rows, const int32_t* total_rows, hipStream_t s) {
+void launch_layernorm_bf16(const float* y, bf16_t* x, float2* stats, const float* gamma, const float* beta,
+                           float eps, int hidden, int64_t max_rows, const int32_t* total_rows, hipStream_t s) {
     const dim3 grid((unsigned)(max_rows / 4)), block(256);
-#define PS_LN(N) hipLaunchKernelGGL(layernorm_bf16_kernel<N>, grid, block, 0, s, in, out, gamma, beta, eps, total_rows)
+#define PS_LN(N) hipLaunchKernelGGL(layernorm_bf16_kernel<N>, grid, block, 0, s, y, x, stats, gamma, beta, eps, total_rows)
     switch (hidden / 256) {
         case 1: PS_LN(1); break;
         case 2: PS_LN(2); break;
@@ -72,16 +70,23 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
     const ps_model_info& f = m->info;
     const int H = f.hidden, F = f.ffn;
     bf16_t *x = (bf16_t*)ws.x, *qk = (bf16_t*)ws.qkv, *vt = (bf16_t*)ws.vt, *att = (bf16_t*)ws.att,
-           *y = (bf16_t*)ws.y, *x1 = (bf16_t*)ws.x1, *g = (bf16_t*)ws.g;
+           *x1 = (bf16_t*)ws.x1, *g = (bf16_t*)ws.g;
     const int32_t* rows = &ws.meta->total_rows;
+    const ResidualSrc none = {nullptr, nullptr, nullptr, nullptr};
+    // the stream entering layer 0 is the embedding LayerNorm of the sums the embed kernel left in ya
+    const float *sg = m->lne_g, *sbeta = m->lne_b;
     for (int l = 0; l < f.layers; ++l) {
         const LayerWeights& w = m->layers[(size_t)l];
-        launch_gemm_bf16(EPI_QKV, x, (const bf16_t*)w.w_qkv, w.b_qkv, nullptr, qk, vt, ws.max_rows, 3 * H, H, H, rows, s);
+        launch_gemm_bf16(EPI_QKV, x, (const bf16_t*)w.w_qkv, w.b_qkv, none, qk, vt, ws.max_rows, 3 * H, H, H, rows, s);
         launch_attention_bf16(m, n_req, ws, s);
-        launch_gemm_bf16(EPI_BIAS_RESIDUAL, att, (const bf16_t*)w.w_o, w.b_o, x, y, nullptr, ws.max_rows, H, H, H, rows, s);
-        launch_layernorm_bf16(y, x1, w.ln1_g, w.ln1_b, m->ln_eps, H, ws.max_rows, rows, s);
-        launch_gemm_bf16(EPI_BIAS_GELU, x1, (const bf16_t*)w.w_1, w.b_1, nullptr, g, nullptr, ws.max_rows, F, H, H, rows, s);
-        launch_gemm_bf16(EPI_BIAS_RESIDUAL, g, (const bf16_t*)w.w_2, w.b_2, x1, y, nullptr, ws.max_rows, H, F, H, rows, s);
-        launch_layernorm_bf16(y, x, w.ln2_g, w.ln2_b, m->ln_eps, H, ws.max_rows, rows, s);
+        const ResidualSrc in = {ws.ya, ws.sa, sg, sbeta};
+        launch_gemm_bf16(EPI_BIAS_RESIDUAL, att, (const bf16_t*)w.w_o, w.b_o, in, ws.yb, nullptr, ws.max_rows, H, H, H, rows, s);
+        launch_layernorm_bf16(ws.yb, x1, ws.sb, w.ln1_g, w.ln1_b, m->ln_eps, H, ws.max_rows, rows, s);
+        launch_gemm_bf16(EPI_BIAS_GELU, x1, (const bf16_t*)w.w_1, w.b_1, none, g, nullptr, ws.max_rows, F, H, H, rows, s);
+        const ResidualSrc mid = {ws.yb, ws.sb, w.ln1_g, w.ln1_b};
+        launch_gemm_bf16(EPI_BIAS_RESIDUAL, g, (const bf16_t*)w.w_2, w.b_2, mid, ws.ya, nullptr, ws.max_rows, H, F, H, rows, s);
+        launch_layernorm_bf16(ws.ya, x, ws.sa, w.ln2_g, w.ln2_b, m->ln_eps, H, ws.max_rows, rows, s);
+        sg = w.ln2_g;
+        sbeta = w.ln2_b;
     }
 }

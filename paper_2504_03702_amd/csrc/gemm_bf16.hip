@@ -2,7 +2,7 @@
 //
 //   C[m, n] = sum_k A[m, k] * W[n, k]   (A: activations [rows][K], W: weights [N][K], both bf16,
 //                                        contraction index contiguous; fp32 accumulation)
-//   epilogue: + bias[n], then one of: store | erf-GELU, store | + residual[m, n], store |
+//   epilogue: + bias[n], then one of: store | erf-GELU, store | + residual stream, store fp32 |
 //             QKV split (query and key columns to [rows][2H], value columns transposed to
 //             Vt[H][max_rows] so the attention kernel reads keys-contiguous value tiles).
 //
@@ -55,9 +55,12 @@ __device__ __forceinline__ void dma_slice(const unsigned char* base, unsigned la
                                           unsigned char* lds, int wave) {
 #pragma unroll
     for (int j = 0; j < ROWS / 8 / NW; ++j) {
+        // readfirstlane returns a signed int: widen through unsigned, or a low word with bit 31
+        // set would sign-extend into the high word
         const uint64_t u = (uint64_t)(base + (int64_t)j * (NW * 8) * ld_bytes);
-        const unsigned char* ub = (const unsigned char*)(((uint64_t)__builtin_amdgcn_readfirstlane((unsigned)(u >> 32)) << 32) |
-                                                        __builtin_amdgcn_readfirstlane((unsigned)u));
+        const uint64_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(u >> 32));
+        const uint64_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)u);
+        const unsigned char* ub = (const unsigned char*)((hi << 32) | lo);
         const unsigned char* g = ub + lane_off;
         __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)g, (LDS_AS void*)(lds + (j * NW + wave) * 1024),
                                          16, 0, 0);
@@ -67,7 +70,7 @@ __device__ __forceinline__ void dma_slice(const unsigned char* base, unsigned la
 template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
-    const bf16_t* __restrict__ residual, bf16_t* __restrict__ C, bf16_t* __restrict__ Vt, int64_t vt_ld,
+    ResidualSrc res, void* __restrict__ Cv, bf16_t* __restrict__ Vt, int64_t vt_ld,
     int N, int K, int hidden, const int32_t* __restrict__ total_rows) {
     using T = Tile<BM, BN, WM, WN>;
     // two stages, each an A slice followed by a W slice
@@ -179,12 +182,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
 
     // ---- epilogue: accumulator element e of tile (i, j) is C[row, col] with
     //      row = 32 i + 8 (e / 4) + 4 (lane / 32) + e % 4,  col = 32 j + lane % 32 -------------
+    bf16_t* C = (bf16_t*)Cv;
     const int row_base = m0 + wm * (BM / WM) + 4 * fhalf;
     const int col_base = n0 + wn * (BN / WN) + frow;
 #pragma unroll
     for (int j = 0; j < T::TN; ++j) {
         const int col = col_base + 32 * j;
         const float bv = bias[col];
+        float rg = 0.f, rb = 0.f;
+        if (EPI == EPI_BIAS_RESIDUAL) { rg = res.gamma[col]; rb = res.beta[col]; }
 #pragma unroll
         for (int i = 0; i < T::TM; ++i) {
 #pragma unroll
@@ -198,8 +204,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
                     for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
                 }
                 if (EPI == EPI_BIAS_RESIDUAL) {
+                    // the stream is LayerNorm(y_prev), recomputed in fp32 from the row statistics;
+                    // the new sums stay in fp32 so the stream is never rounded to bf16
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] += bf16_to_f32(residual[(int64_t)(row + e) * N + col]);
+                    for (int e = 0; e < 4; ++e) {
+                        const float2 st = res.stats[row + e];
+                        const float yp = res.y[(int64_t)(row + e) * N + col];
+                        v[e] += (yp - st.x) * st.y * rg + rb;
+                        ((float*)Cv)[(int64_t)(row + e) * N + col] = v[e];
+                    }
+                    continue;
                 }
                 if (EPI == EPI_QKV) {
                     if (col >= 2 * hidden) {
@@ -220,8 +234,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
 }
 
 template <int BM, int BN, int WM, int WN>
-void launch_cfg(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias, const bf16_t* residual,
-                bf16_t* C, bf16_t* vt, int64_t max_rows, int N, int K, int hidden, const int32_t* total_rows,
+void launch_cfg(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias, ResidualSrc residual,
+                void* C, bf16_t* vt, int64_t max_rows, int N, int K, int hidden, const int32_t* total_rows,
                 hipStream_t s) {
     const int64_t tiles = (max_rows + BM - 1) / BM * (N / BN);
     const dim3 grid((unsigned)((tiles + 7) / 8 * 8)), block(WM * WN * 64);
@@ -242,7 +256,7 @@ void launch_cfg(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float*
 // Requirements (checked when the model is loaded): N % 256 == 0, K % 64 == 0; every buffer holds
 // max_rows rows with max_rows % 256 == 0, so whole tiles are always in bounds.
 void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias,
-                      const bf16_t* residual, bf16_t* C, bf16_t* vt, int64_t max_rows, int N, int K,
+                      ResidualSrc residual, void* C, bf16_t* vt, int64_t max_rows, int N, int K,
                       int hidden, const int32_t* total_rows, hipStream_t s) {
     launch_cfg<256, 256, 2, 2>(epi, A, W, bias, residual, C, vt, max_rows, N, K, hidden, total_rows, s);
 }

@@ -53,6 +53,10 @@ struct Workspace {
     int32_t *qtile_start;        // [B+1] first attention query tile of request r
     int32_t *bad_req;            // [B]   set when a request's text holds an invalid token id
     void *x, *qkv, *vt, *att, *y, *x1, *g;
+    // bf16 path: the residual stream is kept in fp32 as the pre-LayerNorm sums of the last two
+    // sublayers plus each row's (mean, 1/std); its LayerNorm is recomputed wherever it is needed
+    float *ya, *yb;
+    float2 *sa, *sb;
     int64_t max_rows;            // rows every activation buffer holds (multiple of PS_ROW_TILE)
     int64_t max_qtiles;
     size_t bytes;
@@ -65,19 +69,28 @@ void launch_prep(const ps_model* m, const int32_t* offsets, const int32_t* lengt
                  const Workspace& ws, ps_status* st, hipStream_t s);
 void launch_embed(const ps_model* m, const int32_t* token_ids, const int32_t* offsets, int32_t n_req,
                   const Workspace& ws, ps_status* st, hipStream_t s);
-void launch_head(const ps_model* m, int32_t n_req, const Workspace& ws, const void* x_final,
-                 float* pred_f, int32_t* pred_tokens, ps_status* st, hipStream_t s);
+void launch_head(const ps_model* m, int32_t n_req, const Workspace& ws, float* pred_f, int32_t* pred_tokens,
+                 ps_status* st, hipStream_t s);
 void run_encoder_f32(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s);
 void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s);
 
 // bf16 kernels
 enum GemmEpilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2, EPI_QKV = 3 };
+// The residual stream entering a sublayer: LayerNorm(y) with the row statistics already known.
+struct ResidualSrc {
+    const float* y;          // [rows][hidden] fp32 pre-LayerNorm sums
+    const float2* stats;     // [rows] (mean, 1 / sqrt(var + eps))
+    const float* gamma;
+    const float* beta;
+};
 // C[rows, N] = A[rows, K] * W^T (+ epilogue); W is [N][K]; rows = *total_rows (device).
+// EPI_BIAS_RESIDUAL writes fp32 sums (C is float*); the other epilogues write bf16.
 void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias,
-                      const bf16_t* residual, bf16_t* C, bf16_t* vt, int64_t max_rows, int N, int K,
+                      ResidualSrc res, void* C, bf16_t* vt, int64_t max_rows, int N, int K,
                       int hidden, const int32_t* total_rows, hipStream_t s);
 void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s);
-void launch_layernorm_bf16(const bf16_t* in, bf16_t* out, const float* gamma, const float* beta,
+// x = bf16(LayerNorm(y)) and stats = (mean, 1/std) for every live row of the fp32 sums y.
+void launch_layernorm_bf16(const float* y, bf16_t* x, float2* stats, const float* gamma, const float* beta,
                            float eps, int hidden, int64_t max_rows, const int32_t* total_rows,
                            hipStream_t s);
 

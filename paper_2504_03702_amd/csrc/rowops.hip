@@ -86,13 +86,16 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
                                                     int vocab, int n_soft, const BatchMeta* meta,
                                                     const int32_t* __restrict__ seq_len,
                                                     const int32_t* __restrict__ row_start,
-                                                    int32_t* bad_req, T* __restrict__ x, ps_status* st) {
+                                                    int32_t* bad_req, T* __restrict__ x,
+                                                    float* __restrict__ y_out, float2* __restrict__ stats_out,
+                                                    ps_status* st) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int total = meta->total_rows;
     const int64_t live = ((int64_t)total + PS_ROW_TILE - 1) / PS_ROW_TILE * PS_ROW_TILE;
     if (row >= live) return;
     T* out = x + row * H;
+    float* yrow = y_out ? y_out + row * H : nullptr;     // bf16 path: the fp32 sums and row statistics
     int r = -1, p = 0;
     if (row < total) {
         int lo = 0, hi = n_req - 1;          // largest r with row_start[r] <= row
@@ -105,7 +108,11 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
     }
     const int S = r >= 0 ? seq_len[r] : 0;
     if (r < 0 || p >= S) {
-        for (int i = lane; i < H; i += 64) store_elem<T>(out, i, 0.f);
+        for (int i = lane; i < H; i += 64) {
+            store_elem<T>(out, i, 0.f);
+            if (yrow) yrow[i] = 0.f;
+        }
+        if (yrow && lane == 0) stats_out[row] = make_float2(0.f, 0.f);
         return;
     }
     const int n_text = S - n_soft;
@@ -118,7 +125,11 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
                 report_fault(st, PS_ST_BAD_TOKEN, r);
                 bad_req[r] = 1;
             }
-            for (int i = lane; i < H; i += 64) store_elem<T>(out, i, 0.f);
+            for (int i = lane; i < H; i += 64) {
+                store_elem<T>(out, i, 0.f);
+                if (yrow) yrow[i] = 0.f;
+            }
+            if (yrow && lane == 0) stats_out[row] = make_float2(0.f, 0.f);
             return;
         }
         src = e_tok + (int64_t)id * H;
@@ -138,11 +149,14 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
     for (int i = lane; i < H; i += 64) {
         const float e = load_elem<T>(src, i) + load_elem<T>(pos, i);
         store_elem<T>(out, i, (e - mean) * rstd * gamma[i] + beta[i]);
+        if (yrow) yrow[i] = e;
     }
+    if (yrow && lane == 0) stats_out[row] = make_float2(mean, rstd);
 }
 
 // ------------------------------------------------------------------------------------------
-// head: one workgroup per request.  c = final state of the request's first row; every wavefront
+// head: one workgroup per request.  c = final state of the request's first row (bf16 path: the
+// last LayerNorm recomputed in fp32 from the row's sums and statistics); every wavefront
 // takes hidden units j = wave, wave + 4, ...: a 64-lane dot product of c with row j of W_h1^T
 // reduced across the wavefront, ReLU, times w_h2[j]; the four partial sums are added in a fixed
 // order.  pred_tokens = clamp(rint(y), 0, d_max) with rint rounding half to even.
@@ -150,7 +164,10 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
 template <typename T>
 __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, const int32_t* __restrict__ seq_len,
                                                    const int32_t* __restrict__ row_start,
-                                                   const int32_t* __restrict__ bad_req, int H, int Hh,
+                                                   const int32_t* __restrict__ bad_req,
+                                                   const float* __restrict__ y, const float2* __restrict__ stats,
+                                                   const float* __restrict__ ln_g, const float* __restrict__ ln_b,
+                                                   int H, int Hh,
                                                    const float* __restrict__ w_h1t, const float* __restrict__ b_h1,
                                                    const float* __restrict__ w_h2, float b_h2, int d_max,
                                                    float* __restrict__ pred_f, int32_t* __restrict__ pred_tokens,
@@ -165,8 +182,14 @@ __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, cons
         }
         return;
     }
-    const T* c = x + (int64_t)row_start[r] * H;
-    for (int i = threadIdx.x; i < H; i += 256) s_c[i] = load_elem<T>(c, i);
+    const int64_t crow = row_start[r];
+    if (y) {
+        const float2 st2 = stats[crow];
+        for (int i = threadIdx.x; i < H; i += 256) s_c[i] = (y[crow * H + i] - st2.x) * st2.y * ln_g[i] + ln_b[i];
+    } else {
+        const T* c = x + crow * H;
+        for (int i = threadIdx.x; i < H; i += 256) s_c[i] = load_elem<T>(c, i);
+    }
     __syncthreads();
     float acc = 0.f;
     for (int j = wave; j < Hh; j += 4) {
@@ -207,24 +230,26 @@ void launch_embed(const ps_model* m, const int32_t* token_ids, const int32_t* of
         hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, token_ids, offsets, n_req,
                            (const bf16_t*)m->e_tok, (const bf16_t*)m->e_pos, (const bf16_t*)m->e_soft,
                            m->lne_g, m->lne_b, m->ln_eps, f.hidden, f.vocab, f.n_soft, ws.meta, ws.seq_len,
-                           ws.row_start, ws.bad_req, (bf16_t*)ws.x, st);
+                           ws.row_start, ws.bad_req, (bf16_t*)ws.x, ws.ya, ws.sa, st);
     else
         hipLaunchKernelGGL(embed_kernel<float>, dim3(blocks), dim3(256), 0, s, token_ids, offsets, n_req,
                            (const float*)m->e_tok, (const float*)m->e_pos, (const float*)m->e_soft,
                            m->lne_g, m->lne_b, m->ln_eps, f.hidden, f.vocab, f.n_soft, ws.meta, ws.seq_len,
-                           ws.row_start, ws.bad_req, (float*)ws.x, st);
+                           ws.row_start, ws.bad_req, (float*)ws.x, (float*)nullptr, (float2*)nullptr, st);
 }
 
-void launch_head(const ps_model* m, int32_t n_req, const Workspace& ws, const void* x_final,
-                 float* pred_f, int32_t* pred_tokens, ps_status* st, hipStream_t s) {
+void launch_head(const ps_model* m, int32_t n_req, const Workspace& ws, float* pred_f, int32_t* pred_tokens,
+                 ps_status* st, hipStream_t s) {
     const ps_model_info& f = m->info;
     const size_t lds = sizeof(float) * (size_t)(f.hidden + 4);
     if (f.dtype == 1)
-        hipLaunchKernelGGL(head_kernel<bf16_t>, dim3(n_req), dim3(256), lds, s, (const bf16_t*)x_final,
-                           ws.seq_len, ws.row_start, ws.bad_req, f.hidden, f.head_hidden, m->w_h1t, m->b_h1, m->w_h2,
+        hipLaunchKernelGGL(head_kernel<bf16_t>, dim3(n_req), dim3(256), lds, s, (const bf16_t*)ws.x,
+                           ws.seq_len, ws.row_start, ws.bad_req, (const float*)ws.ya, (const float2*)ws.sa,
+                           (const float*)m->layers.back().ln2_g, (const float*)m->layers.back().ln2_b, f.hidden, f.head_hidden, m->w_h1t, m->b_h1, m->w_h2,
                            m->b_h2, f.d_max, pred_f, pred_tokens, st);
     else
-        hipLaunchKernelGGL(head_kernel<float>, dim3(n_req), dim3(256), lds, s, (const float*)x_final,
-                           ws.seq_len, ws.row_start, ws.bad_req, f.hidden, f.head_hidden, m->w_h1t, m->b_h1, m->w_h2,
+        hipLaunchKernelGGL(head_kernel<float>, dim3(n_req), dim3(256), lds, s, (const float*)ws.x,
+                           ws.seq_len, ws.row_start, ws.bad_req, (const float*)nullptr, (const float2*)nullptr,
+                           (const float*)nullptr, (const float*)nullptr, f.hidden, f.head_hidden, m->w_h1t, m->b_h1, m->w_h2,
                            m->b_h2, f.d_max, pred_f, pred_tokens, st);
 }
