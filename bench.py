@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: requests predicted per second.
+
+A step is one pass of the whole path over one batch of synthetic prompts already resident in
+HBM: ps_predict_load (gather, encoder, head) followed on the same stream by ps_anticipate on the
+predictions.  Prints one JSON line with the throughput, the roofline of the dominant kernel (the
+bf16 MFMA GEMM; duration from HIP events the library records around every launch in the timed
+region), the anticipator's HBM rate on a long record stream, and the CPU oracle timed on a bounded
+sample of the same workload on this machine's host cores."""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import tempfile
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
+
+# workload name -> (encoder shape, prompt recipe, anticipator recipe, description)
+WORKLOADS = {
+    "tiny": ("tiny", "tiny", "tiny", "2-layer H128 fp32 encoder, 16 prompts of 8-64 tokens; anticipator 4x64"),
+    "bert_base_padded": ("bert_base", "bert_base_padded", "small",
+                         "BERT-base-shaped bf16 encoder, 64 prompts padded to the batch maximum; anticipator 4x64"),
+    "bert_base_varlen": ("bert_base", "bert_base_varlen", "medium",
+                         "BERT-base-shaped bf16 encoder, 1024 packed prompts (lognormal lengths, Zipf ids); "
+                         "anticipator 64x600"),
+    "latency": ("latency", "latency", "small", "6-layer H768 bf16 encoder, micro-batches of 8 prompts; anticipator 4x64"),
+    "production": ("production", "production", "production",
+                   "16-layer H1024 A16 F4096 bf16 encoder, 4096 packed prompts (lognormal(5.5,1.2) in [4,2048]); "
+                   "anticipator 256 instances x 600 buckets, rates 30-60 tok/s"),
+}
+
+
+def encoder_flops(cfg, lengths):
+    """Algorithmic flops of one call on real tokens: GEMMs and attention separately."""
+    H, F, L = cfg.hidden, cfg.ffn, cfg.layers
+    S = lengths.astype(np.float64) + cfg.n_soft
+    gemm = L * S.sum() * (8.0 * H * H + 4.0 * H * F)
+    attn = L * 4.0 * H * (S ** 2).sum()
+    return gemm, attn
+
+
+def time_cpu_oracle(model_path, batch, ant, budget_s=15.0):
+    """The fp64 oracle (predictor + anticipator) on the first requests of the batch, sized for
+    about `budget_s` seconds from a quick probe of this host's fp64 matmul rate."""
+    from oracle import anticipator as oa
+    from oracle import predictor as op
+    model = op.load_model(model_path)
+    a = np.random.default_rng(0).standard_normal((512, 1024))
+    b = np.random.default_rng(1).standard_normal((1024, 1024))
+    t0 = time.perf_counter()
+    for _ in range(3):
+        a @ b
+    rate = 3 * 2 * 512 * 1024 * 1024 / (time.perf_counter() - t0)          # flop/s
+    H, F, L = model["hidden"], model["ffn"], model["layers"]
+    lengths = batch.valid_lengths()
+    per_req = L * (lengths * (8.0 * H * H + 4.0 * H * F) + 4.0 * H * lengths.astype(np.float64) ** 2)
+    n = int(np.searchsorted(np.cumsum(per_req), 0.5 * rate * budget_s)) + 1     # oracle runs at about half the probe rate
+    n = max(1, min(n, batch.n_req))
+    offs = batch.offsets[: n + 1]
+    lens = None if batch.lengths is None else batch.lengths[:n]
+    t0 = time.perf_counter()
+    _, tok = op.predict_load(model, batch.token_ids, offs, lens)
+    oa.anticipate(tok, ant.instance_id[:n], ant.arrival_bucket[:n], ant.rate, ant.n_inst, ant.horizon)
+    dt = time.perf_counter() - t0
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": n / dt, "unit": "requests/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {n} requests ({int(lengths[:n].sum())} tokens) of the batch, fp64 numpy + C, {dt:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="production", choices=sorted(WORKLOADS))
+    ap.add_argument("--stream-records", type=int, default=44_100_000,
+                    help="records of the anticipator bandwidth stream (0 = skip)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2504_03702_amd import binding as ps
+    from paper_2504_03702_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        return 1
+    ps.load_library()
+    dev = torch.device("cuda:0")
+    model_kind, prompt_kind, ant_kind, desc = WORKLOADS[args.workload]
+    cfg = wl.MODELS[model_kind].resolved()
+
+    tmp = tempfile.mkdtemp(prefix="ps_bench_")
+    model_path = os.path.join(tmp, f"{model_kind}.bin")
+    wl.write_model(model_path, cfg, wl.make_weights(cfg, seed=0))
+    model = ps.ps_model_load(model_path, 0)
+    batch = wl.make_prompts(prompt_kind, seed=0)
+    n_req = batch.n_req
+    lengths = batch.valid_lengths()
+    ant = wl.make_anticipator_inputs(ant_kind, seed=0, n=n_req, pred_tokens=np.zeros(n_req, np.int32))
+
+    t32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.int32)).to(dev)
+    ids, offs = t32(batch.token_ids), t32(batch.offsets)
+    lens = None if batch.lengths is None else t32(batch.lengths)
+    inst, arr = t32(ant.instance_id), t32(ant.arrival_bucket)
+    rate = None if ant.rate is None else t32(ant.rate)
+    pred_f = torch.empty(n_req, dtype=torch.float32, device=dev)
+    pred_t = torch.empty(n_req, dtype=torch.int32, device=dev)
+    load = torch.zeros(ant.n_inst * ant.horizon, dtype=torch.int32, device=dev)
+    ovf = torch.zeros(ant.n_inst, dtype=torch.int64, device=dev)
+    ws = ps.alloc_workspace(ps.ps_workspace_bytes(model, ids.numel(), n_req), dev)
+    aws = ps.alloc_workspace(ps.ps_anticipate_workspace_bytes(n_req, ant.n_inst, ant.horizon), dev)
+    status = ps.new_status(dev)
+
+    def step():
+        ps.ps_predict_load(model, ids, offs, lens, pred_f, pred_t, ws, status)
+        ps.ps_anticipate(pred_t, inst, arr, rate, ant.n_inst, ant.horizon, load, ovf, aws, status)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ps.ps_profile_enable(model, True)
+    ps.ps_profile_read(model)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = ps.ps_profile_read(model)
+    ps.ps_profile_enable(model, False)
+    flags, _ = ps.ps_status_read(status)
+    if flags:
+        print(f"bench.py: device status flags {flags:#x}", file=sys.stderr)
+        return 1
+    ms_per_step = 1e3 * dt / args.steps
+
+    gemm_flops, attn_flops = encoder_flops(cfg, lengths)
+    gemm_ms, gemm_launches = prof["gemm"]
+    out = {
+        "metric": "requests predicted/sec (1 GPU)", "value": n_req / (dt / args.steps), "unit": "requests/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == wl.DTYPE_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {desc}", "requests": n_req, "tokens": int(lengths.sum()),
+                   "algorithmic_tflop_per_step": (gemm_flops + attn_flops) / 1e12},
+        "encoder_mfma_frac": (gemm_flops + attn_flops) / (dt / args.steps) / (PEAK_BF16_TFLOPS * 1e12),
+        "kernel_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
+    }
+    if cfg.dtype == wl.DTYPE_BF16 and gemm_launches:
+        # dominant kernel: the bf16 MFMA GEMM (4 launches per layer); algorithmic flops per launch =
+        # 2*K*N flops per token row, i.e. (8 H^2 + 4 H F) per token per layer over its 4 launches
+        per_launch_flops = gemm_flops * args.steps / gemm_launches
+        per_launch_s = gemm_ms * 1e-3 / gemm_launches
+        achieved = per_launch_flops / per_launch_s / 1e12
+        out["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": achieved,
+                           "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                           "traffic": None, "launches_per_step": gemm_launches // args.steps,
+                           "avg_launch_ms": 1e3 * per_launch_s}
+        att_ms = prof["attention"][0]
+        if att_ms > 0:
+            out["attention_tflops"] = attn_flops * args.steps / (att_ms * 1e-3) / 1e12
+
+    # ---- anticipator on a long record stream (the call sizes above are launch-latency bound) ----
+    if args.stream_records > 0:
+        del ws
+        torch.cuda.empty_cache()
+        s_in = wl.make_anticipator_inputs("stream", seed=0, n=args.stream_records)
+        sp, si, sa, sr = t32(s_in.pred_tokens), t32(s_in.instance_id), t32(s_in.arrival_bucket), t32(s_in.rate)
+        sload = torch.zeros(s_in.n_inst * s_in.horizon, dtype=torch.int32, device=dev)
+        sovf = torch.zeros(s_in.n_inst, dtype=torch.int64, device=dev)
+        sws = ps.alloc_workspace(ps.ps_anticipate_workspace_bytes(args.stream_records, s_in.n_inst, s_in.horizon), dev)
+        reps = 10
+        for _ in range(2):
+            ps.ps_anticipate(sp, si, sa, sr, s_in.n_inst, s_in.horizon, sload, sovf, sws, status)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            ps.ps_anticipate(sp, si, sa, sr, s_in.n_inst, s_in.horizon, sload, sovf, sws, status)
+        e1.record()
+        torch.cuda.synchronize()
+        call_s = e0.elapsed_time(e1) * 1e-3 / reps
+        # algorithmic bytes: three int32 per record read, the map read and written once
+        nbytes = 12.0 * args.stream_records + 8.0 * s_in.n_inst * s_in.horizon
+        gbs = nbytes / call_s / 1e9
+        out["anticipator"] = {"bound": "hbm", "records": args.stream_records, "ms_per_call": 1e3 * call_s,
+                              "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                              "records_per_s": args.stream_records / call_s}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = time_cpu_oracle(model_path, batch, ant)
+    try:
+        os.remove(model_path)
+        os.rmdir(tmp)
+    except OSError:
+        pass
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

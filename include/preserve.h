@@ -136,6 +136,20 @@ int ps_anticipate(const int32_t* pred_tokens, const int32_t* instance_id,
                   int32_t* load, int64_t* overflow,
                   void* workspace, size_t workspace_bytes, ps_status* status, void* hip_stream);
 
+/* Kernel-family timing for benchmarks.  While enabled, ps_predict_load() brackets every kernel
+ * launch with HIP events on the call's stream (the paper reports only the predictor's end-to-end
+ * latency, Sec. 4.5; this splits it by kernel).  ps_profile_read() waits for `hip_stream`, adds
+ * up the elapsed time and launch count of each family since the last read into ms[] and
+ * launches[] (host arrays of PS_N_FAMILIES) and clears the record. */
+#define PS_N_FAMILIES 5
+#define PS_FAM_EMBED     0   /* bookkeeping + embedding gather + embedding LayerNorm */
+#define PS_FAM_GEMM      1   /* QKV, output projection and feed-forward GEMMs         */
+#define PS_FAM_ATTENTION 2
+#define PS_FAM_LAYERNORM 3
+#define PS_FAM_HEAD      4   /* [CLS] pooling + regression head                        */
+int ps_profile_enable(ps_model* model, int on);
+int ps_profile_read(ps_model* model, void* hip_stream, double* ms /*host*/, int64_t* launches /*host*/);
+
 /* Wait for `hip_stream` and copy a device ps_status to *out (host). */
 int ps_status_read(const ps_status* status /*device*/, void* hip_stream, ps_status* out /*host*/);
 

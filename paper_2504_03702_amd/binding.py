@@ -20,7 +20,9 @@ PS_ERRORS = {-1: "PS_EINVAL", -2: "PS_EIO", -3: "PS_EFORMAT", -4: "PS_ENOMEM", -
 PS_ST_BAD_TOKEN, PS_ST_BAD_LENGTH, PS_ST_NAN, PS_ST_BAD_RECORD, PS_ST_RANGE = 0x01, 0x02, 0x04, 0x10, 0x20
 
 EXPORTS = ["ps_model_load", "ps_model_free", "ps_model_get_info", "ps_workspace_bytes", "ps_predict_load",
-           "ps_anticipate_workspace_bytes", "ps_anticipate", "ps_status_read", "ps_strerror"]
+           "ps_anticipate_workspace_bytes", "ps_anticipate", "ps_status_read", "ps_strerror",
+           "ps_profile_enable", "ps_profile_read"]
+PS_FAMILIES = ["embed", "gemm", "attention", "layernorm", "head"]
 
 
 class PsError(RuntimeError):
@@ -66,6 +68,10 @@ def load_library() -> ctypes.CDLL:
     lib.ps_anticipate.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp, vp]
     lib.ps_status_read.restype = ctypes.c_int
     lib.ps_status_read.argtypes = [vp, vp, ctypes.POINTER(ps_status)]
+    lib.ps_profile_enable.restype = ctypes.c_int
+    lib.ps_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.ps_profile_read.restype = ctypes.c_int
+    lib.ps_profile_read.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.ps_strerror.restype = ctypes.c_char_p
     lib.ps_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -116,6 +122,18 @@ def ps_model_load(path: str, device: int = 0) -> Model:
     out = ctypes.c_void_p()
     _check(load_library().ps_model_load(os.fsencode(path), device, ctypes.byref(out)), "ps_model_load")
     return Model(out.value, device)
+
+
+def ps_profile_enable(model: Model, on: bool) -> None:
+    _check(load_library().ps_profile_enable(model.handle, int(on)), "ps_profile_enable")
+
+
+def ps_profile_read(model: Model) -> dict:
+    """{family: (milliseconds, launches)} since the last read; waits for the current stream."""
+    n = len(PS_FAMILIES)
+    ms, cnt = (ctypes.c_double * n)(), (ctypes.c_int64 * n)()
+    _check(load_library().ps_profile_read(model.handle, _stream(), ms, cnt), "ps_profile_read")
+    return {f: (float(ms[i]), int(cnt[i])) for i, f in enumerate(PS_FAMILIES)}
 
 
 def ps_workspace_bytes(model: Model, max_tokens: int, max_req: int) -> int:

@@ -302,8 +302,33 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
     return PS_OK;
 }
 
+extern "C" int ps_profile_enable(ps_model* m, int on) {
+    if (!m) return PS_EINVAL;
+    m->profiling = on != 0;
+    return PS_OK;
+}
+
+extern "C" int ps_profile_read(ps_model* m, void* hip_stream, double* ms, int64_t* launches) {
+    if (!m || !ms || !launches) return PS_EINVAL;
+    if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return PS_EHIP;
+    for (int i = 0; i < PS_N_FAMILIES; ++i) { ms[i] = 0; launches[i] = 0; }
+    int rc = PS_OK;
+    for (const ProfRecord& r : m->prof) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, r.start, r.stop) != hipSuccess) rc = PS_EHIP;
+        ms[r.family] += t;
+        launches[r.family] += 1;
+        m->event_pool.push_back(r.start);
+        m->event_pool.push_back(r.stop);
+    }
+    m->prof.clear();
+    return rc;
+}
+
 extern "C" void ps_model_free(ps_model* m) {
     if (!m) return;
+    for (const ProfRecord& r : m->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    for (hipEvent_t e : m->event_pool) (void)hipEventDestroy(e);
     if (m->blob) {
         (void)hipSetDevice(m->device);
         (void)hipFree(m->blob);
@@ -337,11 +362,17 @@ extern "C" int ps_predict_load(ps_model* m, const int32_t* token_ids, const int3
     if (ws.bytes > workspace_bytes) return PS_EWORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
     (void)hipGetLastError();
-    launch_prep(m, offsets, lengths, n_req, ws, status, s);
-    launch_embed(m, token_ids, offsets, n_req, ws, status, s);
+    {
+        ProfScope p(m, PS_FAM_EMBED, s);
+        launch_prep(m, offsets, lengths, n_req, ws, status, s);
+        launch_embed(m, token_ids, offsets, n_req, ws, status, s);
+    }
     if (m->info.dtype == 1) run_encoder_bf16(m, n_req, ws, s);
     else run_encoder_f32(m, n_req, ws, s);
-    launch_head(m, n_req, ws, pred_f, pred_tokens, status, s);
+    {
+        ProfScope p(m, PS_FAM_HEAD, s);
+        launch_head(m, n_req, ws, pred_f, pred_tokens, status, s);
+    }
     return hipGetLastError() == hipSuccess ? PS_OK : PS_EHIP;
 }
 

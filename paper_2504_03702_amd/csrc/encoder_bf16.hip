@@ -75,18 +75,26 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
     const ResidualSrc none = {nullptr, nullptr, nullptr, nullptr};
     // the stream entering layer 0 is the embedding LayerNorm of the sums the embed kernel left in ya
     const float *sg = m->lne_g, *sbeta = m->lne_b;
+#define PS_TIMED(FAM, CALL) do { ProfScope p_(m, FAM, s); CALL; } while (0)
     for (int l = 0; l < f.layers; ++l) {
         const LayerWeights& w = m->layers[(size_t)l];
-        launch_gemm_bf16(EPI_QKV, x, (const bf16_t*)w.w_qkv, w.b_qkv, none, qk, vt, ws.max_rows, 3 * H, H, H, rows, s);
-        launch_attention_bf16(m, n_req, ws, s);
         const ResidualSrc in = {ws.ya, ws.sa, sg, sbeta};
-        launch_gemm_bf16(EPI_BIAS_RESIDUAL, att, (const bf16_t*)w.w_o, w.b_o, in, ws.yb, nullptr, ws.max_rows, H, H, H, rows, s);
-        launch_layernorm_bf16(ws.yb, x1, ws.sb, w.ln1_g, w.ln1_b, m->ln_eps, H, ws.max_rows, rows, s);
-        launch_gemm_bf16(EPI_BIAS_GELU, x1, (const bf16_t*)w.w_1, w.b_1, none, g, nullptr, ws.max_rows, F, H, H, rows, s);
         const ResidualSrc mid = {ws.yb, ws.sb, w.ln1_g, w.ln1_b};
-        launch_gemm_bf16(EPI_BIAS_RESIDUAL, g, (const bf16_t*)w.w_2, w.b_2, mid, ws.ya, nullptr, ws.max_rows, H, F, H, rows, s);
-        launch_layernorm_bf16(ws.ya, x, ws.sa, w.ln2_g, w.ln2_b, m->ln_eps, H, ws.max_rows, rows, s);
+        PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_QKV, x, (const bf16_t*)w.w_qkv, w.b_qkv, none, qk, vt,
+                                               ws.max_rows, 3 * H, H, H, rows, s));
+        PS_TIMED(PS_FAM_ATTENTION, launch_attention_bf16(m, n_req, ws, s));
+        PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, att, (const bf16_t*)w.w_o, w.b_o, in, ws.yb,
+                                               nullptr, ws.max_rows, H, H, H, rows, s));
+        PS_TIMED(PS_FAM_LAYERNORM, launch_layernorm_bf16(ws.yb, x1, ws.sb, w.ln1_g, w.ln1_b, m->ln_eps, H,
+                                                         ws.max_rows, rows, s));
+        PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_GELU, x1, (const bf16_t*)w.w_1, w.b_1, none, g, nullptr,
+                                               ws.max_rows, F, H, H, rows, s));
+        PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, g, (const bf16_t*)w.w_2, w.b_2, mid, ws.ya,
+                                               nullptr, ws.max_rows, H, F, H, rows, s));
+        PS_TIMED(PS_FAM_LAYERNORM, launch_layernorm_bf16(ws.ya, x, ws.sa, w.ln2_g, w.ln2_b, m->ln_eps, H,
+                                                         ws.max_rows, rows, s));
         sg = w.ln2_g;
         sbeta = w.ln2_b;
     }
+#undef PS_TIMED
 }

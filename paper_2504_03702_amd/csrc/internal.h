@@ -23,7 +23,16 @@ struct LayerWeights {
     float *ln1_g, *ln1_b, *ln2_g, *ln2_b;
 };
 
+struct ProfRecord {
+    int family;
+    hipEvent_t start, stop;
+};
+
 struct ps_model {
+    // event records of ps_profile_enable(); mutable so launch code holding a const model can log
+    mutable bool profiling = false;
+    mutable std::vector<ProfRecord> prof;
+    mutable std::vector<hipEvent_t> event_pool;
     ps_model_info info;
     float ln_eps;
     int device;
@@ -93,5 +102,32 @@ void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws
 void launch_layernorm_bf16(const float* y, bf16_t* x, float2* stats, const float* gamma, const float* beta,
                            float eps, int hidden, int64_t max_rows, const int32_t* total_rows,
                            hipStream_t s);
+
+// Brackets the launches made during its lifetime with two events when profiling is on.
+struct ProfScope {
+    const ps_model* m;
+    hipStream_t s;
+    ProfRecord rec;
+    bool live;
+    ProfScope(const ps_model* model, int family, hipStream_t stream) : m(model), s(stream), live(false) {
+        if (!m->profiling) return;
+        hipEvent_t ev[2];
+        for (int i = 0; i < 2; ++i) {
+            if (!m->event_pool.empty()) {
+                ev[i] = m->event_pool.back();
+                m->event_pool.pop_back();
+            } else if (hipEventCreate(&ev[i]) != hipSuccess) {
+                return;
+            }
+        }
+        rec = {family, ev[0], ev[1]};
+        live = hipEventRecord(rec.start, s) == hipSuccess;
+    }
+    ~ProfScope() {
+        if (!live) return;
+        (void)hipEventRecord(rec.stop, s);
+        m->prof.push_back(rec);
+    }
+};
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
