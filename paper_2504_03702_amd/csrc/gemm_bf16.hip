@@ -32,8 +32,33 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // chunk swizzle of LDS row `r` (see the header comment); depends on r mod 16 only
 __device__ __forceinline__ int swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 
+// erf-GELU x * Phi(x) with Phi(x) - 1/2 = x * Q((x / 4.5)^2) on |x| <= 4.5 (Q: degree-8 least-squares
+// fit on Chebyshev nodes) and Phi clamped beyond; absolute error of the result below 6e-5, under the
+// bf16 rounding of the stored value wherever the value is not itself tiny.  A dozen full-rate
+// operations instead of the several dozen of a branching erff.
 __device__ __forceinline__ float gelu_erf(float v) {
-    return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f));
+    const float xc = fminf(fmaxf(v, -4.5f), 4.5f);
+    const float u = xc * (1.0f / 4.5f);
+    const float t = u * u;
+    float q = 8.248823390e-01f;
+    q = fmaf(q, t, -4.479837417e+00f);
+    q = fmaf(q, t, 1.069920200e+01f);
+    q = fmaf(q, t, -1.489329668e+01f);
+    q = fmaf(q, t, 1.354238783e+01f);
+    q = fmaf(q, t, -8.567420454e+00f);
+    q = fmaf(q, t, 3.921988782e+00f);
+    q = fmaf(q, t, -1.335489713e+00f);
+    q = fmaf(q, t, 3.986949891e-01f);
+    return v * fmaf(xc, q, 0.5f);
+}
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+// two floats -> packed bf16 pair with the hardware conversion (round to nearest even)
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+    f32x2_t f = {lo, hi};
+    bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
+    return *reinterpret_cast<uint32_t*>(&b);
 }
 
 template <int BM, int BN, int WM, int WN>
@@ -140,10 +165,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
     };
     // interleave: one LDS read, then its share of the MFMAs
     auto interleave = [&]() {
+        constexpr int nR = T::TM + T::TN, nM = T::TM * T::TN;
 #pragma unroll
-        for (int r = 0; r < T::TM + T::TN; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                   // DS read
-            __builtin_amdgcn_sched_group_barrier(0x008, T::TM * T::TN / (T::TM + T::TN), 0);     // MFMA
+        for (int r = 0; r < nM % nR; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // DS read
+            __builtin_amdgcn_sched_group_barrier(0x008, nM / nR + 1, 0);     // MFMA
+        }
+#pragma unroll
+        for (int r = nM % nR; r < nR; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, nM / nR, 0);
         }
     };
 
@@ -180,54 +211,116 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
         interleave();
     }
 
-    // ---- epilogue: accumulator element e of tile (i, j) is C[row, col] with
-    //      row = 32 i + 8 (e / 4) + 4 (lane / 32) + e % 4,  col = 32 j + lane % 32 -------------
-    bf16_t* C = (bf16_t*)Cv;
-    const int row_base = m0 + wm * (BM / WM) + 4 * fhalf;
-    const int col_base = n0 + wn * (BN / WN) + frow;
+    // ---- epilogue ---------------------------------------------------------------------------------
+    // Accumulator element e of tile (i, j) is C[row, col] with row = 32 i + 8 (e / 4) + 4 (lane / 32)
+    // + e % 4, col = 32 j + lane % 32: a lane holds one column.  The staging buffers are free now
+    // (the last barrier of the loop is behind every wavefront and no DMA is in flight), so each
+    // wavefront transposes through a private LDS region: it writes a strip of accumulators, reads it
+    // back with 16 bytes of consecutive output per lane, applies the epilogue there and issues
+    // 16-byte global accesses that cover whole rows of the strip.
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    float* stg = (float*)(smem + wave * (2 * STAGE / T::NW));
+    const int m_base = m0 + wm * WTM, n_base = n0 + wn * WTN;
+
+    if (EPI == EPI_QKV && n0 >= 2 * hidden) {
+        // value columns go to Vt[feature][row]: stage [32 features][64 rows], rows contiguous
+        constexpr int ST = 64 + 4;
+        static_assert(32 * ST * 4 <= 2 * (T::A_BYTES + T::B_BYTES) / T::NW, "staging region");
+        const float bv_unused = 0.f; (void)bv_unused;
 #pragma unroll
-    for (int j = 0; j < T::TN; ++j) {
-        const int col = col_base + 32 * j;
-        const float bv = bias[col];
-        float rg = 0.f, rb = 0.f;
-        if (EPI == EPI_BIAS_RESIDUAL) { rg = res.gamma[col]; rb = res.beta[col]; }
+        for (int j = 0; j < T::TN; ++j) {
+            const float bj = bias[n_base + 32 * j + frow];
+#pragma unroll
+            for (int ih = 0; ih < T::TM / 2; ++ih) {
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        const f32x16& a = acc[2 * ih + i2][j];
+                        float4 v = make_float4(a[4 * e4] + bj, a[4 * e4 + 1] + bj, a[4 * e4 + 2] + bj, a[4 * e4 + 3] + bj);
+                        *(float4*)(stg + frow * ST + 32 * i2 + 8 * e4 + 4 * fhalf) = v;
+                    }
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int c = (lane >> 3) + 8 * it, rg = lane & 7;
+                    const float4 lo = *(const float4*)(stg + c * ST + 8 * rg);
+                    const float4 hi = *(const float4*)(stg + c * ST + 8 * rg + 4);
+                    const uint4 o = make_uint4(cvt_pk_bf16(lo.x, lo.y), cvt_pk_bf16(lo.z, lo.w),
+                                               cvt_pk_bf16(hi.x, hi.y), cvt_pk_bf16(hi.z, hi.w));
+                    *(uint4*)(Vt + (int64_t)(n_base - 2 * hidden + 32 * j + c) * vt_ld + m_base + 64 * ih + 8 * rg) = o;
+                }
+            }
+        }
+        return;
+    }
+
+    constexpr int SW = WTN + 4;                        // staging row stride in floats
+    static_assert(32 * SW * 4 <= 2 * (T::A_BYTES + T::B_BYTES) / T::NW, "staging region");
+    auto stage_strip = [&](int i) {
+#pragma unroll
+        for (int j = 0; j < T::TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                stg[(8 * (e >> 2) + 4 * fhalf + (e & 3)) * SW + 32 * j + frow] = acc[i][j][e];
+    };
+
+    if (EPI == EPI_BIAS_RESIDUAL) {
+        // fp32 sums out: v = acc + bias + LayerNorm(y_prev) recomputed from the row statistics, so
+        // the residual stream is never rounded to bf16.  A lane handles 4 consecutive columns.
+        constexpr int LPR = WTN / 4, RPI = 64 / LPR;
+        const int cg = lane % LPR, r_in = lane / LPR;
+        const int col = n_base + 4 * cg;
+        const float4 bv = *(const float4*)(bias + col);
+        const float4 rg = *(const float4*)(res.gamma + col);
+        const float4 rb = *(const float4*)(res.beta + col);
+        float* Cf = (float*)Cv;
 #pragma unroll
         for (int i = 0; i < T::TM; ++i) {
+            stage_strip(i);
 #pragma unroll
-            for (int e4 = 0; e4 < 4; ++e4) {
-                const int row = row_base + 32 * i + 8 * e4;
-                float v[4];
+            for (int it = 0; it < 32 / RPI; ++it) {
+                const int r = r_in + RPI * it;
+                const int64_t row = m_base + 32 * i + r;
+                const float4 a = *(const float4*)(stg + r * SW + 4 * cg);
+                const float2 st = res.stats[row];
+                const float4 yp = *(const float4*)(res.y + row * N + col);
+                float4 o;
+                o.x = a.x + bv.x + ((yp.x - st.x) * st.y * rg.x + rb.x);
+                o.y = a.y + bv.y + ((yp.y - st.x) * st.y * rg.y + rb.y);
+                o.z = a.z + bv.z + ((yp.z - st.x) * st.y * rg.z + rb.z);
+                o.w = a.w + bv.w + ((yp.w - st.x) * st.y * rg.w + rb.w);
+                *(float4*)(Cf + row * N + col) = o;
+            }
+        }
+        return;
+    }
+
+    {
+        // bf16 out (plain, GELU, or the query / key columns of the QKV projection): 8 columns per lane
+        constexpr int LPR = WTN / 8, RPI = 64 / LPR;
+        const int cg = lane % LPR, r_in = lane / LPR;
+        const int col = n_base + 8 * cg;
+        const float4 b0 = *(const float4*)(bias + col), b1 = *(const float4*)(bias + col + 4);
+        const int64_t ldc = EPI == EPI_QKV ? 2 * (int64_t)hidden : (int64_t)N;
+        bf16_t* C = (bf16_t*)Cv;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * e4 + e] + bv;
+        for (int i = 0; i < T::TM; ++i) {
+            stage_strip(i);
+#pragma unroll
+            for (int it = 0; it < 32 / RPI; ++it) {
+                const int r = r_in + RPI * it;
+                const int64_t row = m_base + 32 * i + r;
+                const float4 lo = *(const float4*)(stg + r * SW + 8 * cg);
+                const float4 hi = *(const float4*)(stg + r * SW + 8 * cg + 4);
+                float v[8] = {lo.x + b0.x, lo.y + b0.y, lo.z + b0.z, lo.w + b0.w,
+                              hi.x + b1.x, hi.y + b1.y, hi.z + b1.z, hi.w + b1.w};
                 if (EPI == EPI_BIAS_GELU) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
+                    for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);
                 }
-                if (EPI == EPI_BIAS_RESIDUAL) {
-                    // the stream is LayerNorm(y_prev), recomputed in fp32 from the row statistics;
-                    // the new sums stay in fp32 so the stream is never rounded to bf16
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float2 st = res.stats[row + e];
-                        const float yp = res.y[(int64_t)(row + e) * N + col];
-                        v[e] += (yp - st.x) * st.y * rg + rb;
-                        ((float*)Cv)[(int64_t)(row + e) * N + col] = v[e];
-                    }
-                    continue;
-                }
-                if (EPI == EPI_QKV) {
-                    if (col >= 2 * hidden) {
-                        // value columns: 4 consecutive tokens of one feature row of Vt
-                        uint2 p = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-                        *(uint2*)(Vt + (int64_t)(col - 2 * hidden) * vt_ld + row) = p;
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) C[(int64_t)(row + e) * (2 * hidden) + col] = f32_to_bf16(v[e]);
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) C[(int64_t)(row + e) * N + col] = f32_to_bf16(v[e]);
-                }
+                const uint4 o = make_uint4(cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3]),
+                                           cvt_pk_bf16(v[4], v[5]), cvt_pk_bf16(v[6], v[7]));
+                *(uint4*)(C + row * ldc + col) = o;
             }
         }
     }
@@ -258,5 +351,5 @@ void launch_cfg(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float*
 void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias,
                       ResidualSrc residual, void* C, bf16_t* vt, int64_t max_rows, int N, int K,
                       int hidden, const int32_t* total_rows, hipStream_t s) {
-    launch_cfg<256, 256, 2, 2>(epi, A, W, bias, residual, C, vt, max_rows, N, K, hidden, total_rows, s);
+    launch_cfg<256, 256, 2, 4>(epi, A, W, bias, residual, C, vt, max_rows, N, K, hidden, total_rows, s);
 }
