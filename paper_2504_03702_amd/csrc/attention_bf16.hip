@@ -11,8 +11,11 @@
 // and the softmax needs one cross-lane exchange per tile (between the two half-wavefronts that
 // hold different keys of the same query).  The accumulator layout of S^T is, up to the order of the
 // contraction index (which A and B only have to agree on), the B-operand layout of the second
-// product, so P never leaves registers.  The 1/sqrt(64) scale is folded into the query projection
-// when the model is loaded.  The value tile is read keys-contiguous from the transposed copy Vt
+// product, so P never leaves registers.  Which key sits in which accumulator row is free too (it
+// is just the LDS row a lane reads its K fragment from): rows are assigned so that the 8 scores a
+// lane contributes to one step of the second product belong to 8 consecutive keys, and the
+// matching value fragment is a single 16-byte LDS read.  The 1/sqrt(64) scale is folded into the
+// query projection when the model is loaded.  The value tile is read keys-contiguous from the transposed copy Vt
 // that the QKV projection's epilogue writes.
 //
 // Keys beyond the request's length in the last tile are excluded: their scores are set to -inf
@@ -28,8 +31,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define GLOBAL_AS __attribute__((address_space(1)))
 #define LDS_AS __attribute__((address_space(3)))
-
-__device__ __forceinline__ int swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 
 union Frag8 {
     bf16x8 v;
@@ -83,8 +84,10 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
         for (int j = 0; j < 2; ++j) {
             const int grp = j * 4 + wave;
             const int r = grp * 8 + drow;                     // key row (K tile) / feature row (V^T tile)
-            const int c = (lane & 7) ^ swz(r);
-            const bf16_t* gk = qk + (int64_t)min(base + k0 + r, last_row) * ld_qk + H + head * 64 + c * 8;
+            const int c = (lane & 7) ^ lds_swz(r);
+            // LDS row r of the K tile holds the key with bits 2 and 3 of r swapped (see below)
+            const int kr = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);
+            const bf16_t* gk = qk + (int64_t)min(base + k0 + kr, last_row) * ld_qk + H + head * 64 + c * 8;
             __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)gk, (LDS_AS void*)(sK + grp * 1024), 16, 0, 0);
             const bf16_t* gv = vt + (int64_t)(head * 64 + r) * vt_ld + base + k0 + c * 8;
             __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)gv, (LDS_AS void*)(sV + grp * 1024), 16, 0, 0);
@@ -92,12 +95,16 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     };
 
     // ---- LDS fragment offsets ---------------------------------------------------------------------
-    int koff[4];                                              // K tile: row col, chunk 2ks + half
+    // K tile: the DMA stores key (r with bits 2 and 3 swapped) in LDS row r, so accumulator row r of a
+    // 32-key block is that key.  Accumulator element e of half-wave h is row 8 (e / 4) + 4 h + e % 4,
+    // hence key 16 (e / 8) + 8 h + e % 8 of the block: elements 8 j .. 8 j + 7 are the 8 consecutive
+    // keys 16 j + 8 h + 0..7.  Lanes read rows in natural order, which keeps the reads conflict-free.
+    int koff[4];                                              // chunk 2 ks + half of row col
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) koff[ks] = col * 128 + (((2 * ks + half) ^ swz(col)) * 16);
-    int voff[8];                                              // V^T tile: row col, chunk c, 8-byte half
+    for (int ks = 0; ks < 4; ++ks) koff[ks] = col * 128 + (((2 * ks + half) ^ lds_swz(col)) * 16);
+    int voff[4];                                              // V^T tile: feature row col, key chunk 2 j + half
 #pragma unroll
-    for (int c = 0; c < 8; ++c) voff[c] = col * 128 + ((c ^ swz(col)) * 16) + 8 * half;
+    for (int j = 0; j < 4; ++j) voff[j] = col * 128 + (((2 * j + half) ^ lds_swz(col)) * 16);
 
     f32x16 o[2];
 #pragma unroll
@@ -130,14 +137,14 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
                 s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[b], 0, 0, 0);
             }
         }
-        // element e of block b is key k0 + 32 b + 8 (e / 4) + 4 half + e % 4
+        // element e of block b is key k0 + 32 b + 16 (e / 8) + 8 half + 4 ((e / 4) % 2) + e % 4
         const bool partial = k0 + BK > S;                     // uniform
         if (partial) {
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const int key = k0 + 32 * b + 8 * (e >> 2) + 4 * half + (e & 3);
+                    const int key = k0 + 32 * b + 16 * (e >> 3) + 8 * half + (e & 7);
                     if (key >= S) s[b][e] = -INFINITY;
                 }
         }
@@ -162,34 +169,33 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
                     const float p0 = __builtin_amdgcn_exp2f(fmaf(s[b][8 * j + 2 * t], LOG2E, -mb));
                     const float p1 = __builtin_amdgcn_exp2f(fmaf(s[b][8 * j + 2 * t + 1], LOG2E, -mb));
                     psum += p0 + p1;
-                    pf[b][j].u[t] = pack_bf16x2(p0, p1);
+                    pf[b][j].u[t] = cvt_pk_bf16(p0, p1);
                 }
         l_run = l_run * alpha + psum;
+        if (__any(alpha != 1.0f)) {       // once the maxima have settled the accumulators need no rescale
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
+                for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
+        }
 
-        // O^T += V^T P^T.  Step (b, j) contracts keys 32 b + 16 j + {4 half + 0..3, 8 + 4 half + 0..3},
-        // the keys the P fragment holds, so the value fragment is two 8-byte reads.
+        // O^T += V^T P^T.  Step (b, j) contracts keys 32 b + 16 j + 8 half + 0..7 in this lane, the keys
+        // its P fragment holds in that order: the value fragment is key chunk 4 b + 2 j + half.
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const int c0 = 4 * b + 2 * j;
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
                     Frag8 vf;
-                    vf.h[0] = *(const uint2*)(sV + i * 4096 + voff[c0]);
-                    vf.h[1] = *(const uint2*)(sV + i * 4096 + voff[c0 + 1]);
+                    vf.v = *(const bf16x8*)(sV + i * 4096 + voff[2 * b + j]);
                     if (partial) {
-                        // zero the value entries of keys beyond the request
-                        const int key = k0 + 32 * b + 16 * j + 4 * half;
+                        // zero the value entries of keys beyond the request (they may hold anything)
+                        const int key = k0 + 32 * b + 16 * j + 8 * half;
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
-                            const int kk = key + (t >> 1) * 8 + (t & 1) * 2;     // keys kk, kk + 1
                             uint32_t w = vf.u[t];
-                            if (kk >= S) w = 0; else if (kk + 1 >= S) w &= 0xffffu;
+                            if (key + 2 * t >= S) w = 0; else if (key + 2 * t + 1 >= S) w &= 0xffffu;
                             vf.u[t] = w;
                         }
                     }
@@ -208,8 +214,8 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int e4 = 0; e4 < 4; ++e4) {
-                const uint2 p = make_uint2(pack_bf16x2(o[i][4 * e4] * inv, o[i][4 * e4 + 1] * inv),
-                                           pack_bf16x2(o[i][4 * e4 + 2] * inv, o[i][4 * e4 + 3] * inv));
+                const uint2 p = make_uint2(cvt_pk_bf16(o[i][4 * e4] * inv, o[i][4 * e4 + 1] * inv),
+                                           cvt_pk_bf16(o[i][4 * e4 + 2] * inv, o[i][4 * e4 + 3] * inv));
                 *(uint2*)(orow + 32 * i + 8 * e4 + 4 * half) = p;
             }
     }

@@ -21,6 +21,20 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
+typedef __bf16 ps_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float ps_f32x2 __attribute__((ext_vector_type(2)));
+// Two floats -> packed bf16 pair with the hardware conversion (round to nearest even).
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+    ps_f32x2 f = {lo, hi};
+    ps_bf16x2 b = __builtin_convertvector(f, ps_bf16x2);
+    return *reinterpret_cast<uint32_t*>(&b);
+}
+
+// XOR swizzle of the 16-byte chunks of a 128-byte LDS row: chunk c of row r lives at position
+// c ^ lds_swz(r).  Any 8 consecutive rows, and any 16 consecutive rows taken modulo two rows, then
+// fall in different banks for a 16-byte read per lane.  Depends on r mod 16 only.
+__device__ __forceinline__ int lds_swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

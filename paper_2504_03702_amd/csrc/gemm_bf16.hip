@@ -29,9 +29,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 #define GLOBAL_AS __attribute__((address_space(1)))
 #define LDS_AS __attribute__((address_space(3)))
 
-// chunk swizzle of LDS row `r` (see the header comment); depends on r mod 16 only
-__device__ __forceinline__ int swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
-
 // erf-GELU x * Phi(x) with Phi(x) - 1/2 = x * Q((x / 4.5)^2) on |x| <= 4.5 (Q: degree-8 least-squares
 // fit on Chebyshev nodes) and Phi clamped beyond; absolute error of the result below 6e-5, under the
 // bf16 rounding of the stored value wherever the value is not itself tiny.  A dozen full-rate
@@ -50,15 +47,6 @@ __device__ __forceinline__ float gelu_erf(float v) {
     q = fmaf(q, t, -1.335489713e+00f);
     q = fmaf(q, t, 3.986949891e-01f);
     return v * fmaf(xc, q, 0.5f);
-}
-
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-// two floats -> packed bf16 pair with the hardware conversion (round to nearest even)
-__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
-    f32x2_t f = {lo, hi};
-    bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
-    return *reinterpret_cast<uint32_t*>(&b);
 }
 
 template <int BM, int BN, int WM, int WN>
@@ -118,7 +106,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
 
     // ---- DMA sources: lane i of a wavefront fetches chunk (i%8)^swz of row i/8 of its group ----
     const int dma_row = wave * 8 + (lane >> 3);
-    const int dma_chunk = (lane & 7) ^ swz(dma_row);
+    const int dma_chunk = (lane & 7) ^ lds_swz(dma_row);
     const unsigned lane_off = (unsigned)(dma_row * K + dma_chunk * 8) * 2u;
     const int64_t ld_bytes = (int64_t)K * 2;
     const unsigned char* ga = (const unsigned char*)(A + (int64_t)m0 * K);      // wave-uniform
@@ -130,7 +118,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
     const int b_off = (wn * (BN / WN) + frow) * 128;
     int koff[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) koff[ks] = ((2 * ks + fhalf) ^ swz(frow)) * 16;
+    for (int ks = 0; ks < 4; ++ks) koff[ks] = ((2 * ks + fhalf) ^ lds_swz(frow)) * 16;
 
     f32x16 acc[T::TM][T::TN];
 #pragma unroll
