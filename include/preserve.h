@@ -57,10 +57,10 @@ typedef struct ps_status {
                                     instance outside [0, n_inst), arrival outside [0, horizon),
                                     or rate[instance] < 1                                     */
 #define PS_ST_RANGE        0x20  /* a load bucket left the int32 range (its low 32 bits are stored),
-                                    or a workgroup folded so many tokens (2^27 per wavefront)
+                                    or a workgroup folded so many tokens (2^28 per wavefront)
                                     that it cannot rule that out                              */
 
-#define PS_MAX_PRED  (1 << 24)   /* largest pred_tokens value ps_anticipate accepts           */
+#define PS_MAX_PRED  (1 << 19)   /* largest pred_tokens value ps_anticipate accepts           */
 
 typedef struct ps_model ps_model;   /* opaque; owns the device copy of the weights */
 
@@ -128,8 +128,9 @@ size_t ps_anticipate_workspace_bytes(int64_t n_req, int32_t n_inst, int32_t hori
  *             aligned.
  *   status    device ps_status or NULL.  Faulty records are skipped (PS_ST_BAD_RECORD).
  * Integer arithmetic throughout: the result does not depend on record order and is bit-exact.
- * Errors: PS_EINVAL, PS_EWORKSPACE, PS_EUNSUPPORTED (horizon too long for one row of the map
- * to fit a compute unit's local memory), PS_EHIP.  n_req == 0 is allowed. */
+ * pred_tokens, instance_id and arrival_bucket must be 16-byte aligned (PS_EINVAL otherwise).
+ * Errors: PS_EINVAL, PS_EWORKSPACE, PS_EUNSUPPORTED (horizon above 65535, or too long for one row
+ * of the map to fit a compute unit's local memory), PS_EHIP.  n_req == 0 is allowed. */
 int ps_anticipate(const int32_t* pred_tokens, const int32_t* instance_id,
                   const int32_t* arrival_bucket, const int32_t* rate,
                   int64_t n_req, int32_t n_inst, int32_t horizon,

@@ -8,12 +8,15 @@
 //
 // Kernel 1 (scatter): the map's rows are split into groups that fit one compute unit's LDS as
 // difference arrays; the records are split into slices.  Workgroup (group, slice) streams its
-// slice with coalesced loads and applies the updates of the records whose instance is in its
-// group to its private LDS rows, then writes the rows to a partial buffer.  The groups of one
-// slice are placed on the same XCD so the slice is fetched from HBM once and shared through L2.
+// slice with coalesced 16-byte loads (four records per lane).  Each wavefront compacts the records
+// whose instance is in its group into a small LDS queue (ballot + prefix count, no atomics) and,
+// whenever 64 are queued, applies them with every lane busy: two exact divisions by float
+// reciprocal and three LDS adds into the workgroup's private rows.  At the end the rows go to a
+// partial buffer.  The groups of one slice are placed on the same XCD so the slice is fetched from
+// HBM once and shared through that XCD's L2.
 // Kernel 2 (reduce): one workgroup per instance sums the partial difference rows, takes the prefix
 // sum over buckets and accumulates into load[]; overflow[] likewise.  No global atomics: every
-// global word has exactly one writer.  All arithmetic is integer, so the result is exact and
+// global word has exactly one writer; the only atomic operations are the LDS adds of kernel 1.  All arithmetic is integer, so the result is exact and
 // independent of record order.
 #include <string.h>
 
@@ -23,7 +26,10 @@
 namespace {
 
 const int kLdsBytes = 160 * 1024;        // LDS of one gfx950 compute unit
-const int kScatterThreads = 1024;
+const int kWaves = 8;                    // wavefronts per scatter workgroup
+const int kScatterThreads = kWaves * 64;
+const int kQueue = 128;                  // entries of a wavefront's compaction queue
+const int kQueueBytes = kWaves * kQueue * 8;
 const int64_t kMinSlice = 16384;         // records per slice below which more slices do not pay
 const int kTargetWorkgroups = 256;       // one scatter workgroup per compute unit
 
@@ -37,9 +43,11 @@ struct AntPlan {
 AntPlan make_plan(int64_t n, int n_inst, int horizon) {
     AntPlan p;
     memset(&p, 0, sizeof(p));
-    const int64_t per_row = 4 * (int64_t)horizon + 8 + 4;      // difference row + overflow + rate
-    const int64_t fit = (kLdsBytes - 64) / per_row;
+    if (horizon > 65535) return p;                              // arrival buckets are queued as 16 bits
+    const int64_t per_row = 4 * (int64_t)horizon + 8 + 8;      // difference row + overflow + (rate, 1/rate)
+    int64_t fit = (kLdsBytes - kQueueBytes - 64) / per_row;
     if (fit < 1) return p;
+    if (fit > 65535) fit = 65535;                               // row-in-group is queued as 16 bits
     p.groups = (int)((n_inst + fit - 1) / fit);
     p.rows_per_group = (n_inst + p.groups - 1) / p.groups;
     int64_t s = (n + kMinSlice - 1) / kMinSlice;
@@ -48,8 +56,8 @@ AntPlan make_plan(int64_t n, int n_inst, int horizon) {
     if (s < 1) s = 1;
     p.slices = (int)s;
     p.slice_len = (n + s - 1) / s;
-    p.slice_len = (p.slice_len + 3) / 4 * 4;
-    p.lds_bytes = (size_t)(p.rows_per_group * per_row);
+    p.slice_len = (p.slice_len + 3) / 4 * 4;                    // slices start on 16-byte boundaries
+    p.lds_bytes = (size_t)(p.rows_per_group * per_row + kQueueBytes + 64);
     p.partial_bytes = align_up((size_t)p.slices * n_inst * horizon * 4, 256);
     p.ovf_bytes = align_up((size_t)p.slices * n_inst * 8, 256);
     p.total_bytes = p.partial_bytes + p.ovf_bytes;
@@ -57,12 +65,27 @@ AntPlan make_plan(int64_t n, int n_inst, int horizon) {
     return p;
 }
 
+// Exact integer division by float reciprocals.  All numerators here are below 2^20
+// (pred_tokens <= PS_MAX_PRED = 2^19, rates clamped to 2^19, which changes no result because a rate
+// above the prediction already gives a duration of one bucket).  For a numerator N < 2^20 and a
+// divisor d, let x = N / d.  An estimate e with x < x (1 + 2.5 * 2^-23) <= e <= x (1 + 1.3 * 2^-20) has
+// floor(e) = floor(x): e is never below x, and x is either an integer or at least 1/d below the
+// next one, while e - x <= N * 1.3 * 2^-20 / d < 1/d.  Both estimates below stay inside that band:
+//   - row reciprocal: fl(fl(1/r) * (1 + 2^-21)), then one multiply: factors (1 + 2^-21)(1 +- 2^-24)^3;
+//   - v_rcp_f32 (1 ulp) times N times (1 + 2^-20): factors (1 + 2^-20)(1 +- 2^-23)(1 +- 2^-24)^2.
+__device__ __forceinline__ unsigned div_by_row(unsigned num, float biased_rcp) {
+    return (unsigned)((float)num * biased_rcp);
+}
+__device__ __forceinline__ unsigned div_exact(unsigned num, unsigned den) {
+    return (unsigned)(((float)num * __builtin_amdgcn_rcpf((float)den)) * (1.0f + 0x1p-20f));
+}
+
 __global__ __launch_bounds__(kScatterThreads) void anticipate_scatter_kernel(
     const int32_t* __restrict__ pred_tokens, const int32_t* __restrict__ instance_id,
     const int32_t* __restrict__ arrival_bucket, const int32_t* __restrict__ rate, int64_t n, int n_inst,
     int horizon, int rows_per_group, int groups, int slices, int64_t slice_len,
     int32_t* __restrict__ partial, int64_t* __restrict__ partial_ovf, ps_status* st) {
-    extern __shared__ __align__(8) unsigned char lds_raw[];
+    extern __shared__ __align__(16) unsigned char lds_raw[];
     // blocks are dealt to the 8 XCDs round-robin: keep the groups of one slice on one XCD
     const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
     const int g = j % groups;
@@ -71,55 +94,116 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_scatter_kernel(
     const int k0 = g * rows_per_group;
     const int rows = min(rows_per_group, n_inst - k0);
     if (rows <= 0) return;
-    unsigned long long* s_ovf = (unsigned long long*)lds_raw;                  // [rows_per_group]
-    int* s_rate = (int*)(s_ovf + rows_per_group);                              // [rows_per_group]
-    int* s_diff = s_rate + rows_per_group;                                     // [rows_per_group][horizon]
-    const int tid = threadIdx.x;
+    uint2* s_queue = (uint2*)lds_raw;                                          // [kWaves][kQueue]
+    int* s_flag = (int*)(lds_raw + kQueueBytes);                               // [1] some row has rate < 1
+    unsigned long long* s_ovf = (unsigned long long*)(lds_raw + kQueueBytes + 64);  // [rows_per_group]
+    int2* s_rr = (int2*)(s_ovf + rows_per_group);                              // (rate, biased 1/rate)
+    int* s_diff = (int*)(s_rr + rows_per_group);                               // [rows_per_group][horizon]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) *s_flag = 0;
+    __syncthreads();
     for (int i = tid; i < rows * horizon; i += kScatterThreads) s_diff[i] = 0;
     for (int i = tid; i < rows; i += kScatterThreads) {
         s_ovf[i] = 0;
-        s_rate[i] = rate ? rate[k0 + i] : 1;
+        int r = rate ? rate[k0 + i] : 1;
+        if (r < 1) { *s_flag = 1; r = 0; }
+        r = min(r, PS_MAX_PRED);
+        const float rcp = r > 0 ? (1.0f / (float)r) * (1.0f + 0x1p-21f) : 0.f;
+        s_rr[i] = make_int2(r, __float_as_int(rcp));
     }
     __syncthreads();
+    const bool bad_rate_rows = *s_flag != 0;                 // uniform; rare
+
+    uint2* q = s_queue + wave * kQueue;
+    unsigned head = 0, tail = 0;                                // wave-uniform ring indices
+    unsigned long long mass = 0;       // bound on the magnitude any difference cell can have reached
+
+    // Apply up to 64 queued records (lane i takes entry head + i): all lanes busy on the divisions.
+    auto consume = [&](unsigned count) {
+        if ((unsigned)lane < count) {
+            const uint2 e = q[(head + lane) & (kQueue - 1)];
+            const unsigned D = e.x, kk = e.y >> 16, a = e.y & 0xffffu;
+            const int2 rr = s_rr[kk];
+            unsigned dur;
+            if (rate) dur = div_by_row(D + (unsigned)rr.x - 1u, __int_as_float(rr.y));
+            else dur = (unsigned)horizon - a;
+            const unsigned qq = div_exact(D, dur);
+            const unsigned rem = D - qq * dur;
+            int* row = s_diff + kk * horizon + a;
+            const unsigned room = (unsigned)horizon - a;        // buckets from a to the end of the row
+            atomicAdd(row, (int)(qq + 1));
+            if (rem < room) atomicAdd(row + rem, -1);
+            if (dur < room) {
+                atomicAdd(row + dur, -(int)qq);
+            } else if (dur > room) {
+                const unsigned long long inside = (unsigned long long)room * qq + min(room, rem);
+                atomicAdd(&s_ovf[kk], (unsigned long long)D - inside);
+            }
+            mass += qq + 1;
+        }
+    };
 
     const int64_t begin = (int64_t)slice * slice_len;
     const int64_t end = min(begin + slice_len, n);
-    unsigned long long mass = 0;      // bound on the magnitude any difference cell can have reached
-    for (int64_t i = begin + tid; i < end; i += kScatterThreads) {
-        const int k = instance_id[i];
-        if ((unsigned)k >= (unsigned)n_inst) {
-            if (g == 0) report_fault(st, PS_ST_BAD_RECORD, i);
-            continue;
+    for (int64_t blk = begin + (int64_t)wave * 256; blk < end; blk += (int64_t)kWaves * 256) {
+        const int64_t idx = blk + lane * 4;
+        int k4[4], d4[4], a4[4];
+        bool suspect = false;
+        if (idx + 3 < end) {
+            const int4 kv = *(const int4*)(instance_id + idx);
+            const int4 dv = *(const int4*)(pred_tokens + idx);
+            const int4 av = *(const int4*)(arrival_bucket + idx);
+            k4[0] = kv.x; k4[1] = kv.y; k4[2] = kv.z; k4[3] = kv.w;
+            d4[0] = dv.x; d4[1] = dv.y; d4[2] = dv.z; d4[3] = dv.w;
+            a4[0] = av.x; a4[1] = av.y; a4[2] = av.z; a4[3] = av.w;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bool in = idx + c < end;
+                k4[c] = in ? instance_id[idx + c] : -1;         // -1 never matches a group
+                d4[c] = in ? pred_tokens[idx + c] : 0;
+                a4[c] = in ? arrival_bucket[idx + c] : 0;
+            }
+            suspect = idx < end;                                // the ragged tail is checked record by record
         }
-        const int kk = k - k0;
-        if ((unsigned)kk >= (unsigned)rows) continue;
-        const int D = pred_tokens[i];
-        const int a = arrival_bucket[i];
-        const int r = s_rate[kk];
-        if ((unsigned)D > (unsigned)PS_MAX_PRED || (unsigned)a >= (unsigned)horizon || r < 1) {
-            report_fault(st, PS_ST_BAD_RECORD, i);
-            continue;
+        // validity of all four records at once; a block with a faulty record takes the slow path
+        const unsigned dmax = max(max((unsigned)d4[0], (unsigned)d4[1]), max((unsigned)d4[2], (unsigned)d4[3]));
+        const unsigned amax = max(max((unsigned)a4[0], (unsigned)a4[1]), max((unsigned)a4[2], (unsigned)a4[3]));
+        const unsigned kmax = max(max((unsigned)k4[0], (unsigned)k4[1]), max((unsigned)k4[2], (unsigned)k4[3]));
+        suspect = suspect || dmax > (unsigned)PS_MAX_PRED || amax >= (unsigned)horizon || kmax >= (unsigned)n_inst;
+        const bool slow = __any(suspect) || bad_rate_rows;      // uniform
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const unsigned kk = (unsigned)(k4[c] - k0);
+            bool m = kk < (unsigned)rows && d4[c] != 0;
+            if (slow) {
+                const bool in = idx + c < end;
+                const bool k_ok = (unsigned)k4[c] < (unsigned)n_inst;
+                bool ok = (unsigned)d4[c] <= (unsigned)PS_MAX_PRED && (unsigned)a4[c] < (unsigned)horizon;
+                if (kk < (unsigned)rows && ok && s_rr[kk].x < 1) ok = false;
+                // a record outside every group is reported by group 0, others by their own group
+                if (in && ((!k_ok && g == 0) || (kk < (unsigned)rows && !ok))) report_fault(st, PS_ST_BAD_RECORD, idx + c);
+                m = m && in && ok;
+            }
+            const unsigned long long mask = __ballot(m);
+            if (mask) {
+                const unsigned pos = tail + __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                                                   __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
+                if (m) q[pos & (kQueue - 1)] = make_uint2((unsigned)d4[c], (kk << 16) | (unsigned)a4[c]);
+                tail += (unsigned)__popcll(mask);
+                if (tail - head >= 64u) {
+                    consume(64u);
+                    head += 64u;
+                }
+            }
         }
-        if (D == 0) continue;
-        const unsigned dur = rate ? ((unsigned)D + (unsigned)r - 1u) / (unsigned)r : (unsigned)(horizon - a);
-        const unsigned q = (unsigned)D / dur;
-        const unsigned rem = (unsigned)D - q * dur;
-        int* row = s_diff + kk * horizon + a;
-        const unsigned room = (unsigned)(horizon - a);      // buckets from a to the end of the row
-        atomicAdd(row, (int)(q + 1));
-        if (rem < room) atomicAdd(row + rem, -1);
-        if (dur < room) {
-            atomicAdd(row + dur, -(int)q);
-        } else if (dur > room) {
-            const unsigned long long inside = (unsigned long long)room * q + min(room, rem);
-            atomicAdd(&s_ovf[kk], (unsigned long long)D - inside);
-        }
-        mass += q + 1;
     }
-    // a cell can only have wrapped if the updates of this workgroup's 16 wavefronts add up to
-    // 2^31 or more, i.e. if some wavefront contributed at least 2^27
+    if (tail != head) consume(tail - head);
+
+    // a cell can only have wrapped if the updates of this workgroup's wavefronts add up to 2^31 or
+    // more, i.e. if some wavefront contributed at least 2^31 / kWaves
     for (int o = 32; o > 0; o >>= 1) mass += __shfl_xor(mass, o, 64);
-    if ((tid & 63) == 0 && mass >= (1ull << 27)) report_fault(st, PS_ST_RANGE, begin);
+    if (lane == 0 && mass >= (1ull << 31) / kWaves) report_fault(st, PS_ST_RANGE, begin);
     __syncthreads();
     int32_t* out = partial + ((int64_t)slice * n_inst + k0) * horizon;
     for (int i = tid; i < rows * horizon; i += kScatterThreads) out[i] = s_diff[i];
@@ -182,6 +266,7 @@ extern "C" int ps_anticipate(const int32_t* pred_tokens, const int32_t* instance
     if (rate && !overflow) return PS_EINVAL;
     if (n_req == 0) return PS_OK;
     if (!pred_tokens || !instance_id || !arrival_bucket || !workspace) return PS_EINVAL;
+    if ((((uintptr_t)pred_tokens | (uintptr_t)instance_id | (uintptr_t)arrival_bucket) & 15) != 0) return PS_EINVAL;
     if ((int64_t)n_inst * horizon > (int64_t)0x7fffffff) return PS_EUNSUPPORTED;
     AntPlan p = make_plan(n_req, n_inst, horizon);
     if (!p.ok) return PS_EUNSUPPORTED;

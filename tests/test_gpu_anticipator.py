@@ -56,9 +56,30 @@ def test_odd_shapes_and_many_groups():
         check(dataclasses.replace(inp, rate=None))
 
 
+def test_divisions_are_exact():
+    """The kernel divides by float reciprocals: every (prediction, rate) pair of a dense grid, and
+    the extremes of the accepted range, must still give the integer quotients."""
+    n_inst = 160
+    rates = np.concatenate([np.arange(1, 151), [1 << 19, (1 << 19) - 1, (1 << 19) + 1, 2**31 - 1, 65536, 65537,
+                                                 4095, 4096, 4097, 1000]]).astype(np.int32)
+    assert rates.shape[0] == n_inst
+    D = np.arange(1, 4200, dtype=np.int32)
+    pred = np.tile(D, n_inst)
+    inst = np.repeat(np.arange(n_inst, dtype=np.int32), D.shape[0])
+    arr = (np.arange(pred.shape[0]) % 7).astype(np.int32)
+    print("anticipator division grid", flush=True)
+    check(wl.AnticipatorInputs(pred, inst, arr, rates, n_inst, 900))
+    big = np.array([1 << 19, (1 << 19) - 1, (1 << 19) - 2, 262144, 262143, 500000, 333333, 99991], np.int32)
+    pred = np.tile(big, n_inst)
+    inst = np.repeat(np.arange(n_inst, dtype=np.int32), big.shape[0])
+    arr = (np.arange(pred.shape[0]) % 900).astype(np.int32)
+    check(wl.AnticipatorInputs(pred, inst, arr, rates, n_inst, 900))
+    check(wl.AnticipatorInputs(pred, inst, arr, None, n_inst, 900))       # duration = horizon - arrival
+
+
 def test_bad_records_are_skipped_and_flagged():
     inp = wl.make_anticipator_inputs("small", seed=4, n=500)
-    inp.pred_tokens[[17, 400]] = [-5, 1 << 25]
+    inp.pred_tokens[[17, 400]] = [-5, (1 << 19) + 1]
     inp.instance_id[[99, 250]] = [inp.n_inst, -1]
     inp.arrival_bucket[[33, 480]] = [inp.horizon, -2]
     ok = np.ones(500, bool)
