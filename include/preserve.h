@@ -57,10 +57,10 @@ typedef struct ps_status {
                                     instance outside [0, n_inst), arrival outside [0, horizon),
                                     or rate[instance] < 1                                     */
 #define PS_ST_RANGE        0x20  /* a load bucket left the int32 range (its low 32 bits are stored),
-                                    or a workgroup folded so many tokens (2^28 per wavefront)
+                                    or a workgroup folded so many tokens (2^27 per wavefront)
                                     that it cannot rule that out                              */
 
-#define PS_MAX_PRED  (1 << 19)   /* largest pred_tokens value ps_anticipate accepts           */
+#define PS_MAX_PRED  65535       /* largest pred_tokens value ps_anticipate accepts           */
 
 typedef struct ps_model ps_model;   /* opaque; owns the device copy of the weights */
 

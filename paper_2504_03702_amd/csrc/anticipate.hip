@@ -26,10 +26,10 @@
 namespace {
 
 const int kLdsBytes = 160 * 1024;        // LDS of one gfx950 compute unit
-const int kWaves = 8;                    // wavefronts per scatter workgroup
+const int kWaves = 16;                   // wavefronts per scatter workgroup
 const int kScatterThreads = kWaves * 64;
 const int kQueue = 128;                  // entries of a wavefront's compaction queue
-const int kQueueBytes = kWaves * kQueue * 8;
+const int kQueueBytes = kWaves * kQueue * 4;
 const int64_t kMinSlice = 16384;         // records per slice below which more slices do not pay
 const int kTargetWorkgroups = 256;       // one scatter workgroup per compute unit
 
@@ -43,11 +43,12 @@ struct AntPlan {
 AntPlan make_plan(int64_t n, int n_inst, int horizon) {
     AntPlan p;
     memset(&p, 0, sizeof(p));
-    if (horizon > 65535) return p;                              // arrival buckets are queued as 16 bits
+    if (horizon > 65535) return p;
     const int64_t per_row = 4 * (int64_t)horizon + 8 + 8;      // difference row + overflow + (rate, 1/rate)
     int64_t fit = (kLdsBytes - kQueueBytes - 64) / per_row;
     if (fit < 1) return p;
-    if (fit > 65535) fit = 65535;                               // row-in-group is queued as 16 bits
+    // a queued record names its difference cell (row * horizon + bucket) in 16 bits; LDS capacity
+    // already keeps a group below 2^16 cells
     p.groups = (int)((n_inst + fit - 1) / fit);
     p.rows_per_group = (n_inst + p.groups - 1) / p.groups;
     int64_t s = (n + kMinSlice - 1) / kMinSlice;
@@ -66,8 +67,8 @@ AntPlan make_plan(int64_t n, int n_inst, int horizon) {
 }
 
 // Exact integer division by float reciprocals.  All numerators here are below 2^20
-// (pred_tokens <= PS_MAX_PRED = 2^19, rates clamped to 2^19, which changes no result because a rate
-// above the prediction already gives a duration of one bucket).  For a numerator N < 2^20 and a
+// (pred_tokens <= PS_MAX_PRED < 2^16, rates clamped to PS_MAX_PRED, which changes no result because a
+// rate above the prediction already gives a duration of one bucket; cell indices below 2^16).  For a numerator N < 2^20 and a
 // divisor d, let x = N / d.  An estimate e with x < x (1 + 2.5 * 2^-23) <= e <= x (1 + 1.3 * 2^-20) has
 // floor(e) = floor(x): e is never below x, and x is either an integer or at least 1/d below the
 // next one, while e - x <= N * 1.3 * 2^-20 / d < 1/d.  Both estimates below stay inside that band:
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_scatter_kernel(
     const int k0 = g * rows_per_group;
     const int rows = min(rows_per_group, n_inst - k0);
     if (rows <= 0) return;
-    uint2* s_queue = (uint2*)lds_raw;                                          // [kWaves][kQueue]
+    uint32_t* s_queue = (uint32_t*)lds_raw;                                    // [kWaves][kQueue]
     int* s_flag = (int*)(lds_raw + kQueueBytes);                               // [1] some row has rate < 1
     unsigned long long* s_ovf = (unsigned long long*)(lds_raw + kQueueBytes + 64);  // [rows_per_group]
     int2* s_rr = (int2*)(s_ovf + rows_per_group);                              // (rate, biased 1/rate)
@@ -114,22 +115,25 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_scatter_kernel(
     __syncthreads();
     const bool bad_rate_rows = *s_flag != 0;                 // uniform; rare
 
-    uint2* q = s_queue + wave * kQueue;
+    uint32_t* q = s_queue + wave * kQueue;
+    const float rcp_horizon = (1.0f / (float)horizon) * (1.0f + 0x1p-21f);
     unsigned head = 0, tail = 0;                                // wave-uniform ring indices
     unsigned long long mass = 0;       // bound on the magnitude any difference cell can have reached
 
     // Apply up to 64 queued records (lane i takes entry head + i): all lanes busy on the divisions.
     auto consume = [&](unsigned count) {
         if ((unsigned)lane < count) {
-            const uint2 e = q[(head + lane) & (kQueue - 1)];
-            const unsigned D = e.x, kk = e.y >> 16, a = e.y & 0xffffu;
+            // entry: difference cell of the arrival bucket (row * horizon + bucket) | prediction
+            const uint32_t e = q[(head + lane) & (kQueue - 1)];
+            const unsigned D = e & 0xffffu, cell = e >> 16;
+            const unsigned kk = div_by_row(cell, rcp_horizon), a = cell - kk * (unsigned)horizon;
             const int2 rr = s_rr[kk];
             unsigned dur;
             if (rate) dur = div_by_row(D + (unsigned)rr.x - 1u, __int_as_float(rr.y));
             else dur = (unsigned)horizon - a;
             const unsigned qq = div_exact(D, dur);
             const unsigned rem = D - qq * dur;
-            int* row = s_diff + kk * horizon + a;
+            int* row = s_diff + cell;
             const unsigned room = (unsigned)horizon - a;        // buckets from a to the end of the row
             atomicAdd(row, (int)(qq + 1));
             if (rem < room) atomicAdd(row + rem, -1);
@@ -145,41 +149,62 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_scatter_kernel(
 
     const int64_t begin = (int64_t)slice * slice_len;
     const int64_t end = min(begin + slice_len, n);
-    for (int64_t blk = begin + (int64_t)wave * 256; blk < end; blk += (int64_t)kWaves * 256) {
+
+    // Four consecutive records per lane, 256 per wavefront and block.  Loads run two blocks ahead of
+    // the block being processed, so six 16-byte loads per lane are in flight while the wavefront works.
+    // The last, partial block of a slice is read record by record.
+    struct Block {
+        int k[4], d[4], a[4];
+        bool ragged;                                            // lane crosses the end of the slice
+    };
+    // Full blocks are loaded unconditionally (straight-line code keeps the memory counter exact, so
+    // a block can be used while the two after it are still in flight); a prefetch past the last
+    // full block is redirected to it and never used.
+    const int64_t n_full = (end - begin) / 256;
+    const int64_t last_full = begin + (n_full - 1) * 256;
+    auto load_full = [&](int64_t blk) {
+        Block b;
+        const int64_t idx = min(blk, last_full) + lane * 4;
+        const int4 kv = *(const int4*)(instance_id + idx);
+        const int4 dv = *(const int4*)(pred_tokens + idx);
+        const int4 av = *(const int4*)(arrival_bucket + idx);
+        b.k[0] = kv.x; b.k[1] = kv.y; b.k[2] = kv.z; b.k[3] = kv.w;
+        b.d[0] = dv.x; b.d[1] = dv.y; b.d[2] = dv.z; b.d[3] = dv.w;
+        b.a[0] = av.x; b.a[1] = av.y; b.a[2] = av.z; b.a[3] = av.w;
+        b.ragged = false;
+        return b;
+    };
+    auto load_ragged = [&](int64_t blk) {
+        Block b;
         const int64_t idx = blk + lane * 4;
-        int k4[4], d4[4], a4[4];
-        bool suspect = false;
-        if (idx + 3 < end) {
-            const int4 kv = *(const int4*)(instance_id + idx);
-            const int4 dv = *(const int4*)(pred_tokens + idx);
-            const int4 av = *(const int4*)(arrival_bucket + idx);
-            k4[0] = kv.x; k4[1] = kv.y; k4[2] = kv.z; k4[3] = kv.w;
-            d4[0] = dv.x; d4[1] = dv.y; d4[2] = dv.z; d4[3] = dv.w;
-            a4[0] = av.x; a4[1] = av.y; a4[2] = av.z; a4[3] = av.w;
-        } else {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const bool in = idx + c < end;
-                k4[c] = in ? instance_id[idx + c] : -1;         // -1 never matches a group
-                d4[c] = in ? pred_tokens[idx + c] : 0;
-                a4[c] = in ? arrival_bucket[idx + c] : 0;
-            }
-            suspect = idx < end;                                // the ragged tail is checked record by record
+        for (int c = 0; c < 4; ++c) {
+            const bool in = idx + c < end;
+            b.k[c] = in ? instance_id[idx + c] : -1;            // -1 never matches a group
+            b.d[c] = in ? pred_tokens[idx + c] : 0;
+            b.a[c] = in ? arrival_bucket[idx + c] : 0;
         }
-        // validity of all four records at once; a block with a faulty record takes the slow path
-        const unsigned dmax = max(max((unsigned)d4[0], (unsigned)d4[1]), max((unsigned)d4[2], (unsigned)d4[3]));
-        const unsigned amax = max(max((unsigned)a4[0], (unsigned)a4[1]), max((unsigned)a4[2], (unsigned)a4[3]));
-        const unsigned kmax = max(max((unsigned)k4[0], (unsigned)k4[1]), max((unsigned)k4[2], (unsigned)k4[3]));
-        suspect = suspect || dmax > (unsigned)PS_MAX_PRED || amax >= (unsigned)horizon || kmax >= (unsigned)n_inst;
+        b.ragged = idx < end;
+        return b;
+    };
+    auto process_block = [&](const Block& b, int64_t blk) {
+        const int64_t idx = blk + lane * 4;
+        // validity of all four records at once; a block with a faulty record, or the ragged tail,
+        // is checked record by record
+        const unsigned dmax = max(max((unsigned)b.d[0], (unsigned)b.d[1]), max((unsigned)b.d[2], (unsigned)b.d[3]));
+        const unsigned amax = max(max((unsigned)b.a[0], (unsigned)b.a[1]), max((unsigned)b.a[2], (unsigned)b.a[3]));
+        const unsigned kmax = max(max((unsigned)b.k[0], (unsigned)b.k[1]), max((unsigned)b.k[2], (unsigned)b.k[3]));
+        const bool suspect = b.ragged || dmax > (unsigned)PS_MAX_PRED || amax >= (unsigned)horizon ||
+                             kmax >= (unsigned)n_inst;
         const bool slow = __any(suspect) || bad_rate_rows;      // uniform
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const unsigned kk = (unsigned)(k4[c] - k0);
-            bool m = kk < (unsigned)rows && d4[c] != 0;
+            const unsigned kk = (unsigned)(b.k[c] - k0);
+            bool m = kk < (unsigned)rows && b.d[c] != 0;
             if (slow) {
                 const bool in = idx + c < end;
-                const bool k_ok = (unsigned)k4[c] < (unsigned)n_inst;
-                bool ok = (unsigned)d4[c] <= (unsigned)PS_MAX_PRED && (unsigned)a4[c] < (unsigned)horizon;
+                const bool k_ok = (unsigned)b.k[c] < (unsigned)n_inst;
+                bool ok = (unsigned)b.d[c] <= (unsigned)PS_MAX_PRED && (unsigned)b.a[c] < (unsigned)horizon;
                 if (kk < (unsigned)rows && ok && s_rr[kk].x < 1) ok = false;
                 // a record outside every group is reported by group 0, others by their own group
                 if (in && ((!k_ok && g == 0) || (kk < (unsigned)rows && !ok))) report_fault(st, PS_ST_BAD_RECORD, idx + c);
@@ -189,7 +214,7 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_scatter_kernel(
             if (mask) {
                 const unsigned pos = tail + __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
                                                                    __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
-                if (m) q[pos & (kQueue - 1)] = make_uint2((unsigned)d4[c], (kk << 16) | (unsigned)a4[c]);
+                if (m) q[pos & (kQueue - 1)] = ((kk * (unsigned)horizon + (unsigned)b.a[c]) << 16) | (unsigned)b.d[c];
                 tail += (unsigned)__popcll(mask);
                 if (tail - head >= 64u) {
                     consume(64u);
@@ -197,7 +222,30 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_scatter_kernel(
                 }
             }
         }
+    };
+
+    const int64_t stride = (int64_t)kWaves * 256;
+    const int64_t blk0 = begin + (int64_t)wave * 256;
+    const int64_t full_end = begin + n_full * 256;
+    if (blk0 < full_end) {
+        // three register sets used in rotation (unrolled, so no set is ever copied: a copy would
+        // have to wait for the load it copies)
+        Block b0 = load_full(blk0);
+        Block b1 = load_full(blk0 + stride);
+        Block b2 = load_full(blk0 + 2 * stride);
+        for (int64_t blk = blk0;;) {
+            process_block(b0, blk);
+            b0 = load_full(blk + 3 * stride);
+            if ((blk += stride) >= full_end) break;
+            process_block(b1, blk);
+            b1 = load_full(blk + 3 * stride);
+            if ((blk += stride) >= full_end) break;
+            process_block(b2, blk);
+            b2 = load_full(blk + 3 * stride);
+            if ((blk += stride) >= full_end) break;
+        }
     }
+    if (full_end < end && wave == (int)(n_full % kWaves)) process_block(load_ragged(full_end), full_end);
     if (tail != head) consume(tail - head);
 
     // a cell can only have wrapped if the updates of this workgroup's wavefronts add up to 2^31 or
@@ -210,37 +258,61 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_scatter_kernel(
     for (int i = tid; i < rows; i += kScatterThreads) partial_ovf[(int64_t)slice * n_inst + k0 + i] = (int64_t)s_ovf[i];
 }
 
+// One workgroup per instance.  Buckets are taken 1024 at a time, thread t owning the four
+// consecutive buckets 4 t .. 4 t + 3: it adds up the partial difference rows (independent loads,
+// four slices in flight), prefix-sums its four values, the 256 thread totals are scanned across the
+// workgroup with wavefront shuffles, and the curve is accumulated into load[].  64-bit sums, so a
+// bucket leaving the int32 range is seen exactly.
 __global__ __launch_bounds__(256) void anticipate_reduce_kernel(const int32_t* __restrict__ partial,
                                                                 const int64_t* __restrict__ partial_ovf,
                                                                 int slices, int n_inst, int horizon,
                                                                 int32_t* __restrict__ load,
                                                                 int64_t* __restrict__ overflow, ps_status* st) {
-    __shared__ long long s_scan[256];
-    const int k = blockIdx.x, tid = threadIdx.x;
+    __shared__ long long s_wave[4];
+    const int k = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t stride = (int64_t)n_inst * horizon;
+    const int32_t* prow = partial + (int64_t)k * horizon;
+    int32_t* lrow = load + (int64_t)k * horizon;
     long long carry = 0;
-    for (int b0 = 0; b0 < horizon; b0 += 256) {
-        const int b = b0 + tid;
-        long long v = 0;
-        if (b < horizon) {
-            const int32_t* p = partial + (int64_t)k * horizon + b;
-            for (int s = 0; s < slices; ++s) v += p[s * stride];
+    for (int b0 = 0; b0 < horizon; b0 += 1024) {
+        const int b = b0 + 4 * tid;
+        long long v[4] = {0, 0, 0, 0};
+        int s = 0;
+        for (; s + 4 <= slices; s += 4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int32_t* p = prow + (s + u) * stride;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) if (b + c < horizon) v[c] += p[b + c];
+            }
         }
-        s_scan[tid] = v;
+        for (; s < slices; ++s) {
+            const int32_t* p = prow + s * stride;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) if (b + c < horizon) v[c] += p[b + c];
+        }
+        v[1] += v[0]; v[2] += v[1]; v[3] += v[2];
+        // inclusive scan of the thread totals: within a wavefront by shuffles, then across the four
+        long long incl = v[3];
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const long long t = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) s_wave[wave] = incl;
         __syncthreads();
-        for (int d = 1; d < 256; d <<= 1) {
-            const long long t = tid >= d ? s_scan[tid - d] : 0;
-            __syncthreads();
-            s_scan[tid] += t;
-            __syncthreads();
+        long long before = carry + incl - v[3];
+        for (int w = 0; w < wave; ++w) before += s_wave[w];
+        const long long total = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (b + c < horizon) {
+                const long long nv = (long long)lrow[b + c] + before + v[c];
+                if (nv > 2147483647ll || nv < -2147483648ll) report_fault(st, PS_ST_RANGE, -1);
+                lrow[b + c] = (int32_t)(uint32_t)(unsigned long long)nv;
+            }
         }
-        const long long incl = carry + s_scan[tid];
-        if (b < horizon) {
-            const long long nv = (long long)load[(int64_t)k * horizon + b] + incl;
-            if (nv > 2147483647ll || nv < -2147483648ll) report_fault(st, PS_ST_RANGE, -1);
-            load[(int64_t)k * horizon + b] = (int32_t)(uint32_t)(unsigned long long)nv;
-        }
-        carry += s_scan[255];
+        carry += total;
         __syncthreads();
     }
     if (tid == 0 && overflow) {
