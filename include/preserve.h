@@ -142,12 +142,13 @@ int ps_anticipate(const int32_t* pred_tokens, const int32_t* instance_id,
  * latency, Sec. 4.5; this splits it by kernel).  ps_profile_read() waits for `hip_stream`, adds
  * up the elapsed time and launch count of each family since the last read into ms[] and
  * launches[] (host arrays of PS_N_FAMILIES) and clears the record. */
-#define PS_N_FAMILIES 5
+#define PS_N_FAMILIES 6
 #define PS_FAM_EMBED     0   /* bookkeeping + embedding gather + embedding LayerNorm */
 #define PS_FAM_GEMM      1   /* QKV, output projection and feed-forward GEMMs         */
 #define PS_FAM_ATTENTION 2
 #define PS_FAM_LAYERNORM 3
 #define PS_FAM_HEAD      4   /* [CLS] pooling + regression head                        */
+#define PS_FAM_REFINE    5   /* error-compensated feed-forward pass over the [CLS] rows */
 int ps_profile_enable(ps_model* model, int on);
 int ps_profile_read(ps_model* model, void* hip_stream, double* ms /*host*/, int64_t* launches /*host*/);
 

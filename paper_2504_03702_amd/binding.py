@@ -22,7 +22,7 @@ PS_ST_BAD_TOKEN, PS_ST_BAD_LENGTH, PS_ST_NAN, PS_ST_BAD_RECORD, PS_ST_RANGE = 0x
 EXPORTS = ["ps_model_load", "ps_model_free", "ps_model_get_info", "ps_workspace_bytes", "ps_predict_load",
            "ps_anticipate_workspace_bytes", "ps_anticipate", "ps_status_read", "ps_strerror",
            "ps_profile_enable", "ps_profile_read"]
-PS_FAMILIES = ["embed", "gemm", "attention", "layernorm", "head"]
+PS_FAMILIES = ["embed", "gemm", "attention", "layernorm", "head", "refine"]
 
 
 class PsError(RuntimeError):

@@ -107,6 +107,9 @@ Workspace plan_workspace(const ps_model_info& info, int64_t n_tokens, int32_t n_
         ws.yb = (float*)take(4 * rows * H);
         ws.sa = (float2*)take(8 * rows);
         ws.sb = (float2*)take(8 * rows);
+        ws.cls_rows = (int64_t)align_up((size_t)(n_req > 0 ? n_req : 1), PS_ROW_TILE);
+        ws.cls_a = take(2 * ws.cls_rows * 2 * H);
+        ws.cls_g = take(2 * ws.cls_rows * 2 * F);
     } else {
         ws.y = take(es * rows * H);
     }
@@ -181,7 +184,7 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
     // Two passes over the same carving code: first sizes, then fills the staging buffer.
     std::vector<uint8_t> stage;
     size_t o_etok = 0, o_epos = 0, o_esoft = 0, o_lneg = 0, o_lneb = 0, o_h1 = 0, o_bh1 = 0, o_wh2 = 0;
-    struct LayerOff { size_t wqkv, wo, w1, w2, bqkv, bo, b1, b2, g1, be1, g2, be2; };
+    struct LayerOff { size_t wqkv, wo, w1, w2, w1d, w2d, bqkv, bo, b1, b2, g1, be1, g2, be2; };
     std::vector<LayerOff> lo((size_t)L);
     for (int pass = 0; pass < 2; ++pass) {
         Carver c;
@@ -248,9 +251,24 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
             t.bo = put_f32(H);
             t.g1 = put_f32(H);
             t.be1 = put_f32(H);
+            auto put_doubled = [&](size_t src_at, int64_t K, int64_t N) {   // [N][K] -> [N][2K], each row twice
+                if (info.dtype != 1) return (size_t)0;
+                size_t at = c.take((size_t)2 * K * N * 2);
+                if (pass) {
+                    const bf16_t* src = (const bf16_t*)(stage.data() + src_at);
+                    bf16_t* dst = (bf16_t*)(stage.data() + at);
+                    for (int64_t n = 0; n < N; ++n) {
+                        memcpy(dst + n * 2 * K, src + n * K, (size_t)K * 2);
+                        memcpy(dst + n * 2 * K + K, src + n * K, (size_t)K * 2);
+                    }
+                }
+                return at;
+            };
             t.w1 = put_matrix(H, F);
+            t.w1d = put_doubled(t.w1, H, F);
             t.b1 = put_f32(F);
             t.w2 = put_matrix(F, H);
+            t.w2d = put_doubled(t.w2, F, H);
             t.b2 = put_f32(H);
             t.g2 = put_f32(H);
             t.be2 = put_f32(H);
@@ -290,6 +308,7 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
         const LayerOff& t = lo[(size_t)l];
         LayerWeights& w = m->layers[(size_t)l];
         w.w_qkv = b + t.wqkv; w.w_o = b + t.wo; w.w_1 = b + t.w1; w.w_2 = b + t.w2;
+        w.w_1d = b + t.w1d; w.w_2d = b + t.w2d;
         w.b_qkv = (float*)(b + t.bqkv); w.b_o = (float*)(b + t.bo);
         w.b_1 = (float*)(b + t.b1); w.b_2 = (float*)(b + t.b2);
         w.ln1_g = (float*)(b + t.g1); w.ln1_b = (float*)(b + t.be1);

@@ -14,10 +14,12 @@
 // different banks.  The swizzle is applied on the global side of the DMA (each lane picks which
 // chunk it fetches), since the LDS side of a DMA is always lane-linear.
 //
-// The number of rows is only known on the device (padded inputs are compacted), so the grid is
-// sized for the host's upper bound and workgroups beyond the live tiles leave at once.  Workgroups
-// are dealt to the 8 XCDs round-robin by the hardware; the tile index is remapped so that each XCD
-// works on a contiguous run of tiles (n fastest), keeping an A row panel hot in that XCD's L2.
+// The kernel is persistent: one workgroup per compute unit walks a list of tiles, prefetching the
+// first k slices of its next tile while the current one finishes, so only the very first tile pays
+// the latency of filling LDS.  The number of rows is only known on the device (padded inputs are
+// compacted); each workgroup derives its tile list from it.  Workgroups are dealt to the 8 XCDs
+// round-robin by the hardware; the tile list is built so that each XCD works on a contiguous run of
+// tiles (n fastest), keeping an A row panel hot in that XCD's L2.
 #include "device_util.h"
 #include "internal.h"
 
@@ -68,12 +70,7 @@ __device__ __forceinline__ void dma_slice(const unsigned char* base, unsigned la
                                           unsigned char* lds, int wave) {
 #pragma unroll
     for (int j = 0; j < ROWS / 8 / NW; ++j) {
-        // readfirstlane returns a signed int: widen through unsigned, or a low word with bit 31
-        // set would sign-extend into the high word
-        const uint64_t u = (uint64_t)(base + (int64_t)j * (NW * 8) * ld_bytes);
-        const uint64_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(u >> 32));
-        const uint64_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)u);
-        const unsigned char* ub = (const unsigned char*)((hi << 32) | lo);
+        const unsigned char* ub = base + (int64_t)j * (NW * 8) * ld_bytes;      // wave-uniform: stays in SGPRs
         const unsigned char* g = ub + lane_off;
         __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)g, (LDS_AS void*)(lds + (j * NW + wave) * 1024),
                                          16, 0, 0);
@@ -86,31 +83,34 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
     ResidualSrc res, void* __restrict__ Cv, bf16_t* __restrict__ Vt, int64_t vt_ld,
     int N, int K, int hidden, const int32_t* __restrict__ total_rows) {
     using T = Tile<BM, BN, WM, WN>;
-    // two stages, each an A slice followed by a W slice
-    __shared__ __align__(1024) unsigned char smem[2 * (T::A_BYTES + T::B_BYTES)];
-    constexpr int STAGE = T::A_BYTES + T::B_BYTES;
+    constexpr int STAGE = T::A_BYTES + T::B_BYTES;      // an A slice followed by a W slice
+    constexpr int EPI_BYTES = 4096;                     // per-wavefront transpose region of the epilogue
+    static_assert(2 * STAGE + T::NW * EPI_BYTES <= 160 * 1024, "LDS budget");
+    __shared__ __align__(1024) unsigned char smem[2 * STAGE + T::NW * EPI_BYTES];
 
-    // ---- which tile ------------------------------------------------------------------------
+    // the wavefront index is uniform; saying so keeps everything derived from it in scalar registers
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    // ---- this workgroup's tiles --------------------------------------------------------------
+    // The grid is persistent (one workgroup per compute unit).  The hardware deals workgroups to the 8
+    // XCDs round-robin; XCD x works through the contiguous run of tiles [x * per_xcd, (x+1) * per_xcd)
+    // (n fastest), its workgroups taking tiles slot, slot + slots, ... of that run, so the tiles in
+    // flight on one XCD at any time are neighbours and share A row panels and W column panels in L2.
     const int rows = *total_rows;
     const int n_tiles = N / BN;
-    const int m_tiles = (rows + BM - 1) / BM;
-    const int tiles = m_tiles * n_tiles;
+    const int tiles = ((rows + BM - 1) / BM) * n_tiles;
     const int per_xcd = (tiles + 7) >> 3;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int tile = xcd * per_xcd + slot;
-    if (slot >= per_xcd || tile >= tiles) return;
-    const int m0 = (tile / n_tiles) * BM, n0 = (tile % n_tiles) * BN;
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave / WN, wn = wave % WN;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
+    const int tile_end = min((xcd + 1) * per_xcd, tiles);
+    int tile = xcd * per_xcd + slot;
+    if (tile >= tile_end) return;
 
     // ---- DMA sources: lane i of a wavefront fetches chunk (i%8)^swz of row i/8 of its group ----
     const int dma_row = wave * 8 + (lane >> 3);
     const int dma_chunk = (lane & 7) ^ lds_swz(dma_row);
     const unsigned lane_off = (unsigned)(dma_row * K + dma_chunk * 8) * 2u;
     const int64_t ld_bytes = (int64_t)K * 2;
-    const unsigned char* ga = (const unsigned char*)(A + (int64_t)m0 * K);      // wave-uniform
-    const unsigned char* gw = (const unsigned char*)(W + (int64_t)n0 * K);
 
     // ---- fragment addresses: row (lane%32) of a 32-row tile, chunks 2*ks + lane/32 ----------
     const int frow = lane & 31, fhalf = lane >> 5;
@@ -121,20 +121,26 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
     for (int ks = 0; ks < 4; ++ks) koff[ks] = ((2 * ks + fhalf) ^ lds_swz(frow)) * 16;
 
     f32x16 acc[T::TM][T::TN];
+    auto clear_acc = [&]() {
 #pragma unroll
-    for (int i = 0; i < T::TM; ++i)
+        for (int i = 0; i < T::TM; ++i)
 #pragma unroll
-        for (int j = 0; j < T::TN; ++j)
+            for (int j = 0; j < T::TN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    };
 
     // Fragment double buffer: while the MFMAs of k-step s run, the ds_reads of step s+1 are in
-    // flight.  Schedule per 64-deep slice kt (stage kt&1 holds it):
+    // flight.  The 64-deep slices of all this workgroup's tiles form one stream, slice g living in
+    // stage g & 1.  Schedule per slice g:
     //   steps 0..2 : read fragments of the next step of this slice | MFMAs of the current step
-    //   then       : wait for this wavefront's DMA of slice kt+1, workgroup barrier (now every
-    //                wavefront has read its last fragments of slice kt and slice kt+1 is visible),
-    //                start the DMA of slice kt+2 into the stage slice kt occupied
-    //   step 3     : read step-0 fragments of slice kt+1 | MFMAs of step 3
+    //   then       : wait for this wavefront's DMA of slice g+1, workgroup barrier (now every
+    //                wavefront has read its last fragments of slice g and slice g+1 is visible),
+    //                start the DMA of slice g+2 into the stage slice g occupied
+    //   step 3     : read step-0 fragments of slice g+1 | MFMAs of step 3
+    // Slices g+1 and g+2 may belong to the next tile: its first two slices land while this tile
+    // finishes and runs its epilogue (which has an LDS region of its own), so a tile starts with
+    // its operands already in LDS.
     bf16x8 fa0[T::TM], fb0[T::TN], fa1[T::TM], fb1[T::TN];
     auto read_frags = [&](bf16x8* fa, bf16x8* fb, const unsigned char* stage, int ks) {
         const unsigned char* sA = stage + a_off + koff[ks];
@@ -151,165 +157,192 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
             for (int j = 0; j < T::TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     };
-    // interleave: one LDS read, then its share of the MFMAs
+    // interleave: a share of the MFMAs, then one LDS read
     auto interleave = [&]() {
         constexpr int nR = T::TM + T::TN, nM = T::TM * T::TN;
 #pragma unroll
         for (int r = 0; r < nM % nR; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // DS read
             __builtin_amdgcn_sched_group_barrier(0x008, nM / nR + 1, 0);     // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // DS read
         }
 #pragma unroll
         for (int r = nM % nR; r < nR; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, nM / nR, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
     };
 
     const int nk = K / 64;
-    dma_slice<BM, T::NW>(ga, lane_off, ld_bytes, smem, wave);
-    dma_slice<BN, T::NW>(gw, lane_off, ld_bytes, smem + T::A_BYTES, wave);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (nk > 1) {
-        dma_slice<BM, T::NW>(ga + 128, lane_off, ld_bytes, smem + STAGE, wave);
-        dma_slice<BN, T::NW>(gw + 128, lane_off, ld_bytes, smem + STAGE + T::A_BYTES, wave);
-    }
-    read_frags(fa0, fb0, smem, 0);
-    for (int kt = 0; kt < nk; ++kt) {
-        unsigned char* cur = smem + (kt & 1) * STAGE;
-        unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
-        read_frags(fa1, fb1, cur, 1);
-        mfma_step(fa0, fb0);
-        interleave();
-        read_frags(fa0, fb0, cur, 2);
-        mfma_step(fa1, fb1);
-        interleave();
-        read_frags(fa1, fb1, cur, 3);
-        mfma_step(fa0, fb0);
-        interleave();
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (kt + 2 < nk) {
-            dma_slice<BM, T::NW>(ga + (kt + 2) * 128, lane_off, ld_bytes, cur, wave);
-            dma_slice<BN, T::NW>(gw + (kt + 2) * 128, lane_off, ld_bytes, cur + T::A_BYTES, wave);
+    // prefetch cursor: the next slice to fetch is slice pf_kt of tile pf_tile (none once pf_tile >= tile_end)
+    int pf_tile = tile, pf_kt = 0, pf_stage = 0;
+    auto prefetch_next = [&]() {
+        if (pf_tile < tile_end) {
+            const int pm0 = (pf_tile / n_tiles) * BM, pn0 = (pf_tile % n_tiles) * BN;
+            const unsigned char* ga = (const unsigned char*)(A + (int64_t)pm0 * K) + pf_kt * 128;
+            const unsigned char* gw = (const unsigned char*)(W + (int64_t)pn0 * K) + pf_kt * 128;
+            unsigned char* dst = smem + pf_stage * STAGE;
+            dma_slice<BM, T::NW>(ga, lane_off, ld_bytes, dst, wave);
+            dma_slice<BN, T::NW>(gw, lane_off, ld_bytes, dst + T::A_BYTES, wave);
+            pf_stage ^= 1;
+            if (++pf_kt == nk) { pf_kt = 0; pf_tile += slots; }
         }
-        if (kt + 1 < nk) read_frags(fa0, fb0, nxt, 0);
-        mfma_step(fa1, fb1);
-        interleave();
-    }
-
-    // ---- epilogue ---------------------------------------------------------------------------------
-    // Accumulator element e of tile (i, j) is C[row, col] with row = 32 i + 8 (e / 4) + 4 (lane / 32)
-    // + e % 4, col = 32 j + lane % 32: a lane holds one column.  The staging buffers are free now
-    // (the last barrier of the loop is behind every wavefront and no DMA is in flight), so each
-    // wavefront transposes through a private LDS region: it writes a strip of accumulators, reads it
-    // back with 16 bytes of consecutive output per lane, applies the epilogue there and issues
-    // 16-byte global accesses that cover whole rows of the strip.
-    constexpr int WTM = BM / WM, WTN = BN / WN;
-    float* stg = (float*)(smem + wave * (2 * STAGE / T::NW));
-    const int m_base = m0 + wm * WTM, n_base = n0 + wn * WTN;
-
-    if (EPI == EPI_QKV && n0 >= 2 * hidden) {
-        // value columns go to Vt[feature][row]: stage [32 features][64 rows], rows contiguous
-        constexpr int ST = 64 + 4;
-        static_assert(32 * ST * 4 <= 2 * (T::A_BYTES + T::B_BYTES) / T::NW, "staging region");
-        const float bv_unused = 0.f; (void)bv_unused;
-#pragma unroll
-        for (int j = 0; j < T::TN; ++j) {
-            const float bj = bias[n_base + 32 * j + frow];
-#pragma unroll
-            for (int ih = 0; ih < T::TM / 2; ++ih) {
-#pragma unroll
-                for (int i2 = 0; i2 < 2; ++i2)
-#pragma unroll
-                    for (int e4 = 0; e4 < 4; ++e4) {
-                        const f32x16& a = acc[2 * ih + i2][j];
-                        float4 v = make_float4(a[4 * e4] + bj, a[4 * e4 + 1] + bj, a[4 * e4 + 2] + bj, a[4 * e4 + 3] + bj);
-                        *(float4*)(stg + frow * ST + 32 * i2 + 8 * e4 + 4 * fhalf) = v;
-                    }
-#pragma unroll
-                for (int it = 0; it < 4; ++it) {
-                    const int c = (lane >> 3) + 8 * it, rg = lane & 7;
-                    const float4 lo = *(const float4*)(stg + c * ST + 8 * rg);
-                    const float4 hi = *(const float4*)(stg + c * ST + 8 * rg + 4);
-                    const uint4 o = make_uint4(cvt_pk_bf16(lo.x, lo.y), cvt_pk_bf16(lo.z, lo.w),
-                                               cvt_pk_bf16(hi.x, hi.y), cvt_pk_bf16(hi.z, hi.w));
-                    *(uint4*)(Vt + (int64_t)(n_base - 2 * hidden + 32 * j + c) * vt_ld + m_base + 64 * ih + 8 * rg) = o;
-                }
-            }
-        }
-        return;
-    }
-
-    constexpr int SW = WTN + 4;                        // staging row stride in floats
-    static_assert(32 * SW * 4 <= 2 * (T::A_BYTES + T::B_BYTES) / T::NW, "staging region");
-    auto stage_strip = [&](int i) {
-#pragma unroll
-        for (int j = 0; j < T::TN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e)
-                stg[(8 * (e >> 2) + 4 * fhalf + (e & 3)) * SW + 32 * j + frow] = acc[i][j][e];
     };
 
-    if (EPI == EPI_BIAS_RESIDUAL) {
-        // fp32 sums out: v = acc + bias + LayerNorm(y_prev) recomputed from the row statistics, so
-        // the residual stream is never rounded to bf16.  A lane handles 4 consecutive columns.
-        constexpr int LPR = WTN / 4, RPI = 64 / LPR;
-        const int cg = lane % LPR, r_in = lane / LPR;
-        const int col = n_base + 4 * cg;
-        const float4 bv = *(const float4*)(bias + col);
-        const float4 rg = *(const float4*)(res.gamma + col);
-        const float4 rb = *(const float4*)(res.beta + col);
-        float* Cf = (float*)Cv;
-#pragma unroll
-        for (int i = 0; i < T::TM; ++i) {
-            stage_strip(i);
-#pragma unroll
-            for (int it = 0; it < 32 / RPI; ++it) {
-                const int r = r_in + RPI * it;
-                const int64_t row = m_base + 32 * i + r;
-                const float4 a = *(const float4*)(stg + r * SW + 4 * cg);
-                const float2 st = res.stats[row];
-                const float4 yp = *(const float4*)(res.y + row * N + col);
-                float4 o;
-                o.x = a.x + bv.x + ((yp.x - st.x) * st.y * rg.x + rb.x);
-                o.y = a.y + bv.y + ((yp.y - st.x) * st.y * rg.y + rb.y);
-                o.z = a.z + bv.z + ((yp.z - st.x) * st.y * rg.z + rb.z);
-                o.w = a.w + bv.w + ((yp.w - st.x) * st.y * rg.w + rb.w);
-                *(float4*)(Cf + row * N + col) = o;
-            }
-        }
-        return;
-    }
+    prefetch_next();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    prefetch_next();
+    read_frags(fa0, fb0, smem, 0);
+    int stage = 0;
+    float* stg = (float*)(smem + 2 * STAGE + wave * EPI_BYTES);
+    constexpr int WTM = BM / WM, WTN = BN / WN;
 
-    {
-        // bf16 out (plain, GELU, or the query / key columns of the QKV projection): 8 columns per lane
-        constexpr int LPR = WTN / 8, RPI = 64 / LPR;
-        const int cg = lane % LPR, r_in = lane / LPR;
-        const int col = n_base + 8 * cg;
-        const float4 b0 = *(const float4*)(bias + col), b1 = *(const float4*)(bias + col + 4);
-        const int64_t ldc = EPI == EPI_QKV ? 2 * (int64_t)hidden : (int64_t)N;
-        bf16_t* C = (bf16_t*)Cv;
+    for (; tile < tile_end; tile += slots) {
+        clear_acc();
+        for (int kt = 0; kt < nk; ++kt) {
+            unsigned char* cur = smem + stage * STAGE;
+            unsigned char* nxt = smem + (stage ^ 1) * STAGE;
+            stage ^= 1;
+            read_frags(fa1, fb1, cur, 1);
+            mfma_step(fa0, fb0);
+            interleave();
+            read_frags(fa0, fb0, cur, 2);
+            mfma_step(fa1, fb1);
+            interleave();
+            read_frags(fa1, fb1, cur, 3);
+            mfma_step(fa0, fb0);
+            interleave();
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            prefetch_next();
+            // step-0 fragments of the next slice (of this tile or of the next one), if there is one
+            if (kt + 1 < nk || tile + slots < tile_end) read_frags(fa0, fb0, nxt, 0);
+            mfma_step(fa1, fb1);
+            interleave();
+        }
+
+        // ---- epilogue -----------------------------------------------------------------------------
+        // Accumulator element e of tile (i, j) is C[row, col] with row = 32 i + 8 (e / 4) + 4 (lane / 32)
+        // + e % 4, col = 32 j + lane % 32: a lane holds one column.  Each wavefront transposes through
+        // its private 4 KB of LDS: it writes a strip of accumulators, reads it back with 16 bytes of
+        // consecutive output per lane, applies the epilogue there and issues 16-byte global accesses.
+        const int m0 = (tile / n_tiles) * BM, n0 = (tile % n_tiles) * BN;
+        const int m_base = m0 + wm * WTM, n_base = n0 + wn * WTN;
+
+        if (EPI == EPI_QKV && n0 >= 2 * hidden) {
+            // Value columns go to Vt[feature][row].  One 32 x 32 accumulator tile at a time is staged as
+            // [32 features][32 rows]; the 16-byte chunks of a feature's rows are XOR-swizzled with the
+            // feature index so the 128-byte-strided writes of the 32 lanes spread over the banks.
 #pragma unroll
-        for (int i = 0; i < T::TM; ++i) {
-            stage_strip(i);
+            for (int j = 0; j < T::TN; ++j) {
+                const float bj = bias[n_base + 32 * j + frow];
 #pragma unroll
-            for (int it = 0; it < 32 / RPI; ++it) {
-                const int r = r_in + RPI * it;
-                const int64_t row = m_base + 32 * i + r;
-                const float4 lo = *(const float4*)(stg + r * SW + 8 * cg);
-                const float4 hi = *(const float4*)(stg + r * SW + 8 * cg + 4);
-                float v[8] = {lo.x + b0.x, lo.y + b0.y, lo.z + b0.z, lo.w + b0.w,
-                              hi.x + b1.x, hi.y + b1.y, hi.z + b1.z, hi.w + b1.w};
-                if (EPI == EPI_BIAS_GELU) {
+                for (int i = 0; i < T::TM; ++i) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        const f32x16& a = acc[i][j];
+                        const float4 v = make_float4(a[4 * e4] + bj, a[4 * e4 + 1] + bj, a[4 * e4 + 2] + bj, a[4 * e4 + 3] + bj);
+                        *(float4*)(stg + frow * 32 + 4 * ((2 * e4 + fhalf) ^ (frow & 7))) = v;
+                    }
+#pragma unroll
+                    for (int it = 0; it < 2; ++it) {
+                        const int c = (lane >> 2) + 16 * it, rg = lane & 3;
+                        const float4 lo = *(const float4*)(stg + c * 32 + 4 * ((2 * rg) ^ (c & 7)));
+                        const float4 hi = *(const float4*)(stg + c * 32 + 4 * ((2 * rg + 1) ^ (c & 7)));
+                        const uint4 o = make_uint4(cvt_pk_bf16(lo.x, lo.y), cvt_pk_bf16(lo.z, lo.w),
+                                                   cvt_pk_bf16(hi.x, hi.y), cvt_pk_bf16(hi.z, hi.w));
+                        *(uint4*)(Vt + (int64_t)(n_base - 2 * hidden + 32 * j + c) * vt_ld + m_base + 32 * i + 8 * rg) = o;
+                    }
                 }
-                const uint4 o = make_uint4(cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3]),
-                                           cvt_pk_bf16(v[4], v[5]), cvt_pk_bf16(v[6], v[7]));
-                *(uint4*)(C + row * ldc + col) = o;
             }
+            continue;
+        }
+
+        // other epilogues: strips of 8 rows x WTN columns, row-major, padded rows
+        constexpr int SW = WTN + 4;
+        static_assert(8 * SW * 4 <= EPI_BYTES && 32 * 32 * 4 <= EPI_BYTES, "epilogue staging region");
+        auto stage_strip = [&](int i, int e4) {      // rows 32 i + 8 e4 + 0..7 of the wavefront's tile
+#pragma unroll
+            for (int j = 0; j < T::TN; ++j)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) stg[(4 * fhalf + t) * SW + 32 * j + frow] = acc[i][j][4 * e4 + t];
+        };
+
+        if (EPI == EPI_BIAS_RESIDUAL || EPI == EPI_RESIDUAL_MAPPED) {
+            // fp32 sums out: v = acc + bias + LayerNorm(y_prev) recomputed from the row statistics, so
+            // the residual stream is never rounded to bf16.  A lane handles 4 consecutive columns.
+            constexpr int LPR = WTN / 4, RPI = 64 / LPR;
+            const int cg = lane % LPR, r_in = lane / LPR;
+            const int col = n_base + 4 * cg;
+            const float4 bv = *(const float4*)(bias + col);
+            const float4 rg = *(const float4*)(res.gamma + col);
+            const float4 rb = *(const float4*)(res.beta + col);
+            float* Cf = (float*)Cv;
+#pragma unroll
+            for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    stage_strip(i, e4);
+#pragma unroll
+                    for (int it = 0; it < 8 / RPI; ++it) {
+                        const int r = r_in + RPI * it;
+                        int64_t row = m_base + 32 * i + 8 * e4 + r;
+                        const float4 a = *(const float4*)(stg + r * SW + 4 * cg);
+                        if (EPI == EPI_RESIDUAL_MAPPED) {
+                            // GEMM row = request; its stream row is the request's first row
+                            if (row >= rows || res.seq_len[row] <= 0) continue;
+                            row = res.row_map[row];
+                        }
+                        const float2 st = res.stats[row];
+                        const float4 yp = *(const float4*)(res.y + row * N + col);
+                        float4 o;
+                        o.x = a.x + bv.x + ((yp.x - st.x) * st.y * rg.x + rb.x);
+                        o.y = a.y + bv.y + ((yp.y - st.x) * st.y * rg.y + rb.y);
+                        o.z = a.z + bv.z + ((yp.z - st.x) * st.y * rg.z + rb.z);
+                        o.w = a.w + bv.w + ((yp.w - st.x) * st.y * rg.w + rb.w);
+                        *(float4*)(Cf + row * N + col) = o;
+                    }
+                }
+            continue;
+        }
+
+        {
+            // bf16 out (plain, GELU, or the query / key columns of the QKV projection): 8 columns per lane
+            constexpr int LPR = WTN / 8, RPI = 64 / LPR;
+            static_assert(RPI == 8, "one 8-row strip per instruction");
+            const int cg = lane % LPR, r = lane / LPR;
+            const int col = n_base + 8 * cg;
+            const float4 b0 = *(const float4*)(bias + col), b1 = *(const float4*)(bias + col + 4);
+            const int64_t ldc = EPI == EPI_QKV ? 2 * (int64_t)hidden : EPI == EPI_GELU_SPLIT ? 2 * (int64_t)N : (int64_t)N;
+            bf16_t* C = (bf16_t*)Cv;
+#pragma unroll
+            for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    stage_strip(i, e4);
+                    const int64_t row = m_base + 32 * i + 8 * e4 + r;
+                    const float4 lo = *(const float4*)(stg + r * SW + 8 * cg);
+                    const float4 hi = *(const float4*)(stg + r * SW + 8 * cg + 4);
+                    float v[8] = {lo.x + b0.x, lo.y + b0.y, lo.z + b0.z, lo.w + b0.w,
+                                  hi.x + b1.x, hi.y + b1.y, hi.z + b1.z, hi.w + b1.w};
+                    if (EPI == EPI_BIAS_GELU || EPI == EPI_GELU_SPLIT) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);
+                    }
+                    const uint4 o = make_uint4(cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3]),
+                                               cvt_pk_bf16(v[4], v[5]), cvt_pk_bf16(v[6], v[7]));
+                    *(uint4*)(C + row * ldc + col) = o;
+                    if (EPI == EPI_GELU_SPLIT) {
+                        // second half of the row: what the first rounding lost, as bf16 again
+                        const uint32_t h[4] = {o.x, o.y, o.z, o.w};
+                        uint32_t l[4];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            l[t] = cvt_pk_bf16(v[2 * t] - __uint_as_float(h[t] << 16),
+                                               v[2 * t + 1] - __uint_as_float(h[t] & 0xffff0000u));
+                        *(uint4*)(C + row * ldc + N + col) = make_uint4(l[0], l[1], l[2], l[3]);
+                    }
+                }
         }
     }
 }
@@ -318,8 +351,10 @@ template <int BM, int BN, int WM, int WN>
 void launch_cfg(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias, ResidualSrc residual,
                 void* C, bf16_t* vt, int64_t max_rows, int N, int K, int hidden, const int32_t* total_rows,
                 hipStream_t s) {
+    // persistent: one workgroup per compute unit (fewer if there cannot be that many tiles)
     const int64_t tiles = (max_rows + BM - 1) / BM * (N / BN);
-    const dim3 grid((unsigned)((tiles + 7) / 8 * 8)), block(WM * WN * 64);
+    const int64_t wgs = tiles < 256 ? (tiles + 7) / 8 * 8 : 256;
+    const dim3 grid((unsigned)wgs), block(WM * WN * 64);
 #define PS_LAUNCH(E)                                                                                       \
     hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, E>), grid, block, 0, s, A, W, bias, residual, C, vt, \
                        max_rows, N, K, hidden, total_rows)
@@ -328,6 +363,8 @@ void launch_cfg(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float*
         case EPI_BIAS_GELU: PS_LAUNCH(EPI_BIAS_GELU); break;
         case EPI_BIAS_RESIDUAL: PS_LAUNCH(EPI_BIAS_RESIDUAL); break;
         case EPI_QKV: PS_LAUNCH(EPI_QKV); break;
+        case EPI_GELU_SPLIT: PS_LAUNCH(EPI_GELU_SPLIT); break;
+        case EPI_RESIDUAL_MAPPED: PS_LAUNCH(EPI_RESIDUAL_MAPPED); break;
     }
 #undef PS_LAUNCH
 }

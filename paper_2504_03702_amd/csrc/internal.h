@@ -19,6 +19,7 @@ typedef uint16_t bf16_t;   // raw bf16 bit pattern
 // (the contraction index contiguous) for the MFMA kernels; fp32 models: float, [in][out].
 struct LayerWeights {
     void *w_qkv, *w_o, *w_1, *w_2;
+    void *w_1d, *w_2d;           // bf16 models: W_1, W_2 with the contraction index repeated ([out][2 in])
     float *b_qkv, *b_o, *b_1, *b_2;
     float *ln1_g, *ln1_b, *ln2_g, *ln2_b;
 };
@@ -51,7 +52,8 @@ struct ps_model {
 struct BatchMeta {
     int32_t total_rows;          // activation rows in use (padded request starts included)
     int32_t total_qtiles;        // attention query tiles over all requests
-    int32_t pad[2];
+    int32_t n_req;               // requests in this call (row count of the per-request side GEMMs)
+    int32_t pad;
 };
 
 // Carved-up workspace of one ps_predict_load call.
@@ -66,6 +68,8 @@ struct Workspace {
     // sublayers plus each row's (mean, 1/std); its LayerNorm is recomputed wherever it is needed
     float *ya, *yb;
     float2 *sa, *sb;
+    void *cls_a, *cls_g;         // per-request rows of the [CLS] refinement: [cls_rows][2H], [cls_rows][2F] bf16
+    int64_t cls_rows;
     int64_t max_rows;            // rows every activation buffer holds (multiple of PS_ROW_TILE)
     int64_t max_qtiles;
     size_t bytes;
@@ -84,19 +88,27 @@ void run_encoder_f32(const ps_model* m, int32_t n_req, const Workspace& ws, hipS
 void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s);
 
 // bf16 kernels
-enum GemmEpilogue { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2, EPI_QKV = 3 };
+enum GemmEpilogue {
+    EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2, EPI_QKV = 3,
+    EPI_GELU_SPLIT = 4,          // GELU, then the fp32 value stored as two bf16 (value ~ hi + lo) in [rows][2N]
+    EPI_RESIDUAL_MAPPED = 5      // EPI_BIAS_RESIDUAL with GEMM row r living at stream row row_map[r]
+};
 // The residual stream entering a sublayer: LayerNorm(y) with the row statistics already known.
 struct ResidualSrc {
     const float* y;          // [rows][hidden] fp32 pre-LayerNorm sums
     const float2* stats;     // [rows] (mean, 1 / sqrt(var + eps))
     const float* gamma;
     const float* beta;
+    const int32_t* row_map;  // EPI_RESIDUAL_MAPPED: stream row of GEMM row r (the request's first row)
+    const int32_t* seq_len;  //                       rows with seq_len[r] <= 0 are not stored
 };
 // C[rows, N] = A[rows, K] * W^T (+ epilogue); W is [N][K]; rows = *total_rows (device).
 // EPI_BIAS_RESIDUAL writes fp32 sums (C is float*); the other epilogues write bf16.
 void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias,
                       ResidualSrc res, void* C, bf16_t* vt, int64_t max_rows, int N, int K,
                       int hidden, const int32_t* total_rows, hipStream_t s);
+void launch_cls_gather(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, const float2* stats,
+                       const float* gamma, const float* beta, hipStream_t s);
 void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s);
 // x = bf16(LayerNorm(y)) and stats = (mean, 1/std) for every live row of the fp32 sums y.
 void launch_layernorm_bf16(const float* y, bf16_t* x, float2* stats, const float* gamma, const float* beta,

@@ -59,6 +59,7 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ 
         qtile_start[n_req] = s_tiles[1023];
         meta->total_rows = s_rows[1023];
         meta->total_qtiles = s_tiles[1023];
+        meta->n_req = n_req;
     }
 }
 
@@ -214,7 +215,37 @@ __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, cons
     }
 }
 
+// Gather for the [CLS] refinement: row r of the side matrix is the fp32 LayerNorm output of request
+// r's first row, split into two bf16 values per element (x ~ hi + lo, |x - hi - lo| <= 2^-17 |x|),
+// hi in columns [0, H), lo in [H, 2H).  Rows of faulty requests and padding rows are zero.
+__global__ __launch_bounds__(256) void cls_gather_kernel(const float* __restrict__ y, const float2* __restrict__ stats,
+                                                         const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                         int H, int n_req, const int32_t* __restrict__ seq_len,
+                                                         const int32_t* __restrict__ row_start, bf16_t* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    bf16_t* o = out + (int64_t)r * 2 * H;
+    if (r >= n_req || seq_len[r] <= 0) {
+        for (int i = lane; i < 2 * H; i += 64) o[i] = 0;
+        return;
+    }
+    const int64_t row = row_start[r];
+    const float2 st = stats[row];
+    for (int i = lane; i < H; i += 64) {
+        const float x = (y[row * H + i] - st.x) * st.y * gamma[i] + beta[i];
+        const bf16_t hi = f32_to_bf16(x);
+        o[i] = hi;
+        o[H + i] = f32_to_bf16(x - bf16_to_f32(hi));
+    }
+}
+
 }  // namespace
+
+void launch_cls_gather(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, const float2* stats,
+                       const float* gamma, const float* beta, hipStream_t s) {
+    hipLaunchKernelGGL(cls_gather_kernel, dim3((unsigned)(ws.cls_rows / 4)), dim3(256), 0, s, y, stats, gamma, beta,
+                       m->info.hidden, n_req, ws.seq_len, ws.row_start, (bf16_t*)ws.cls_a);
+}
 
 void launch_prep(const ps_model* m, const int32_t* offsets, const int32_t* lengths, int32_t n_req,
                  const Workspace& ws, ps_status* st, hipStream_t s) {

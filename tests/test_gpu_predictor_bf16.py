@@ -96,3 +96,66 @@ def test_bert_base_varlen_sampled(tmp_models):
     # the same requests alone give bit-identical results: no cross-request leakage
     alone_f, _, _, _ = run_predict(model, sub)
     assert np.array_equal(alone_f, got_f[pick])
+
+
+def test_latency_shape_micro_batches(tmp_models):
+    """6-layer DistilBERT-shaped encoder on micro-batches of 8 prompts."""
+    print("predict bf16 latency micro-batches", flush=True)
+    cfg = wl.MODELS["latency"]
+    model, ref = make(tmp_models, "latency.bin", cfg)
+    for seed in (0, 1):
+        check(model, ref, wl.make_prompts("latency", seed=seed))
+
+
+def test_production_batch_sampled_and_fused_anticipator(tmp_models):
+    """The benchmark's own launch configuration: 16-layer H1024 encoder, 4096 packed prompts up to
+    2048 tokens, then ps_anticipate over 256 x 600 on the predictions, same stream.  The oracle checks
+    a sample of requests one by one (the longest, the shortest, the first, the last and random ones);
+    the histograms are checked bit-exact against the oracle fed the GPU's own integer predictions, and
+    the totals invariant holds on everything."""
+    import torch
+    from oracle import anticipator as oa
+    print("predict bf16 production 4096 + anticipator", flush=True)
+    cfg = wl.MODELS["production"]
+    model, ref = make(tmp_models, "production.bin", cfg)
+    batch = wl.make_prompts("production", seed=0)
+    n = batch.n_req
+    dev = "cuda:0"
+    ids = torch.from_numpy(batch.token_ids).to(dev)
+    offs = torch.from_numpy(batch.offsets).to(dev)
+    pred_f = torch.empty(n, dtype=torch.float32, device=dev)
+    pred_t = torch.empty(n, dtype=torch.int32, device=dev)
+    ws = ps.alloc_workspace(ps.ps_workspace_bytes(model, ids.numel(), n), dev)
+    ant = wl.make_anticipator_inputs("production", seed=0, n=n, pred_tokens=np.zeros(n, np.int32))
+    t32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.int32)).to(dev)
+    inst, arr, rate = t32(ant.instance_id), t32(ant.arrival_bucket), t32(ant.rate)
+    load = torch.zeros(ant.n_inst * ant.horizon, dtype=torch.int32, device=dev)
+    ovf = torch.zeros(ant.n_inst, dtype=torch.int64, device=dev)
+    aws = ps.alloc_workspace(ps.ps_anticipate_workspace_bytes(n, ant.n_inst, ant.horizon), dev)
+    st = ps.new_status(dev)
+    ps.ps_predict_load(model, ids, offs, None, pred_f, pred_t, ws, st)
+    ps.ps_anticipate(pred_t, inst, arr, rate, ant.n_inst, ant.horizon, load, ovf, aws, st)
+    flags, _ = ps.ps_status_read(st)
+    assert flags == 0
+    got_f, got_t = pred_f.cpu().numpy(), pred_t.cpu().numpy()
+    assert np.isfinite(got_f).all()
+    assert np.array_equal(got_t, np.clip(np.rint(got_f), 0, cfg.d_max).astype(np.int32))
+    # anticipator: bit-exact given identical predicted token counts
+    ref_load, ref_ovf, status, _ = oa.anticipate(got_t, ant.instance_id, ant.arrival_bucket, ant.rate,
+                                                 ant.n_inst, ant.horizon)
+    got_load = load.cpu().numpy().reshape(ant.n_inst, ant.horizon)
+    assert status == 0 and np.array_equal(got_load, ref_load) and np.array_equal(ovf.cpu().numpy(), ref_ovf)
+    per_inst = np.bincount(ant.instance_id, weights=got_t, minlength=ant.n_inst).astype(np.int64)
+    assert np.array_equal(got_load.sum(axis=1, dtype=np.int64) + ovf.cpu().numpy(), per_inst)
+    # predictor: sampled requests against the oracle
+    lengths = batch.valid_lengths()
+    pick = np.unique(np.concatenate([[0, n - 1, int(np.argmax(lengths)), int(np.argmin(lengths))],
+                                     np.random.default_rng(1).choice(n, 6, replace=False)]))
+    sub = wl.pack_prompts(lengths[pick], np.concatenate([batch.token_ids[batch.offsets[r]:batch.offsets[r + 1]] for r in pick]))
+    ref_f, ref_t = op.predict_load(ref, sub.token_ids, sub.offsets)
+    # the scale of the tolerance is the batch's RMS; the sample's RMS stands in for it
+    scale = np.maximum(np.abs(ref_f), np.sqrt(np.mean(ref_f ** 2)))
+    err = np.abs(got_f[pick] - ref_f) / scale
+    print(f"  sampled {len(pick)} requests (lengths {lengths[pick].tolist()}): max rel err {err.max():.3e}", flush=True)
+    assert err.max() < TOL_BF16
+    assert np.all(np.abs(got_t[pick] - ref_t) <= np.ceil(TOL_BF16 * scale) + 1)
