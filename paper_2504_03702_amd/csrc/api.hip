@@ -184,7 +184,7 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
     // Two passes over the same carving code: first sizes, then fills the staging buffer.
     std::vector<uint8_t> stage;
     size_t o_etok = 0, o_epos = 0, o_esoft = 0, o_lneg = 0, o_lneb = 0, o_h1 = 0, o_bh1 = 0, o_wh2 = 0;
-    struct LayerOff { size_t wqkv, wo, w1, w2, w1d, w2d, bqkv, bo, b1, b2, g1, be1, g2, be2; };
+    struct LayerOff { size_t wqkv, wo, w1, w2, wod, w1d, w2d, bqkv, bo, b1, b2, g1, be1, g2, be2; };
     std::vector<LayerOff> lo((size_t)L);
     for (int pass = 0; pass < 2; ++pass) {
         Carver c;
@@ -247,10 +247,6 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
                 }
                 return at;
             };
-            t.wo = put_matrix(H, H);
-            t.bo = put_f32(H);
-            t.g1 = put_f32(H);
-            t.be1 = put_f32(H);
             auto put_doubled = [&](size_t src_at, int64_t K, int64_t N) {   // [N][K] -> [N][2K], each row twice
                 if (info.dtype != 1) return (size_t)0;
                 size_t at = c.take((size_t)2 * K * N * 2);
@@ -264,6 +260,11 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
                 }
                 return at;
             };
+            t.wo = put_matrix(H, H);
+            t.wod = put_doubled(t.wo, H, H);
+            t.bo = put_f32(H);
+            t.g1 = put_f32(H);
+            t.be1 = put_f32(H);
             t.w1 = put_matrix(H, F);
             t.w1d = put_doubled(t.w1, H, F);
             t.b1 = put_f32(F);
@@ -308,7 +309,7 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
         const LayerOff& t = lo[(size_t)l];
         LayerWeights& w = m->layers[(size_t)l];
         w.w_qkv = b + t.wqkv; w.w_o = b + t.wo; w.w_1 = b + t.w1; w.w_2 = b + t.w2;
-        w.w_1d = b + t.w1d; w.w_2d = b + t.w2d;
+        w.w_od = b + t.wod; w.w_1d = b + t.w1d; w.w_2d = b + t.w2d;
         w.b_qkv = (float*)(b + t.bqkv); w.b_o = (float*)(b + t.bo);
         w.b_1 = (float*)(b + t.b1); w.b_2 = (float*)(b + t.b2);
         w.ln1_g = (float*)(b + t.g1); w.ln1_b = (float*)(b + t.be1);

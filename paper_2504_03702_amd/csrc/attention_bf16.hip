@@ -46,6 +46,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     const bf16_t* __restrict__ qk,      // [rows][2H]: query columns then key columns
     const bf16_t* __restrict__ vt,      // [H][vt_ld]: value features x rows
     bf16_t* __restrict__ out,           // [rows][H]
+    bf16_t* __restrict__ cls_out,       // [requests][2H]: first row of every request as hi | lo bf16 pairs
     int H, int64_t vt_ld, int n_req, const BatchMeta* __restrict__ meta,
     const int32_t* __restrict__ seq_len, const int32_t* __restrict__ row_start,
     const int32_t* __restrict__ qtile_start) {
@@ -217,6 +218,17 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
                 const uint2 p = make_uint2(cvt_pk_bf16(o[i][4 * e4] * inv, o[i][4 * e4 + 1] * inv),
                                            cvt_pk_bf16(o[i][4 * e4 + 2] * inv, o[i][4 * e4 + 3] * inv));
                 *(uint2*)(orow + 32 * i + 8 * e4 + 4 * half) = p;
+                if (wq0 + col == 0) {
+                    // the request's first row feeds the head: keep what the bf16 rounding lost as a
+                    // second bf16 value, for the error-compensated output projection of these rows
+                    bf16_t* c = cls_out + (int64_t)lo * 2 * H + head * 64 + 32 * i + 8 * e4 + 4 * half;
+                    *(uint2*)c = p;
+                    const float r0 = o[i][4 * e4] * inv - __uint_as_float(p.x << 16);
+                    const float r1 = o[i][4 * e4 + 1] * inv - __uint_as_float(p.x & 0xffff0000u);
+                    const float r2 = o[i][4 * e4 + 2] * inv - __uint_as_float(p.y << 16);
+                    const float r3 = o[i][4 * e4 + 3] * inv - __uint_as_float(p.y & 0xffff0000u);
+                    *(uint2*)(c + H) = make_uint2(cvt_pk_bf16(r0, r1), cvt_pk_bf16(r2, r3));
+                }
             }
     }
 }
@@ -226,6 +238,6 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s) {
     const dim3 grid((unsigned)ws.max_qtiles, (unsigned)m->info.heads);
     hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16_t*)ws.qkv, (const bf16_t*)ws.vt,
-                       (bf16_t*)ws.att, m->info.hidden, ws.max_rows, n_req, ws.meta, ws.seq_len, ws.row_start,
+                       (bf16_t*)ws.att, (bf16_t*)ws.cls_a, m->info.hidden, ws.max_rows, n_req, ws.meta, ws.seq_len, ws.row_start,
                        ws.qtile_start);
 }

@@ -87,6 +87,11 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
         PS_TIMED(PS_FAM_ATTENTION, launch_attention_bf16(m, n_req, ws, s));
         PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, att, (const bf16_t*)w.w_o, w.b_o, in, ws.yb,
                                                nullptr, ws.max_rows, H, H, H, rows, s));
+        // output projection again for each request's first row from the hi | lo pairs the attention
+        // kernel left in cls_a (see the feed-forward refinement below)
+        const ResidualSrc in_cls = {ws.ya, ws.sa, sg, sbeta, ws.row_start, ws.seq_len};
+        PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_RESIDUAL_MAPPED, (const bf16_t*)ws.cls_a, (const bf16_t*)w.w_od,
+                                                 w.b_o, in_cls, ws.yb, nullptr, ws.cls_rows, H, 2 * H, H, n_req_dev, s));
         PS_TIMED(PS_FAM_LAYERNORM, launch_layernorm_bf16(ws.yb, x1, ws.sb, w.ln1_g, w.ln1_b, m->ln_eps, H,
                                                          ws.max_rows, rows, s));
         PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_GELU, x1, (const bf16_t*)w.w_1, w.b_1, none, g, nullptr,

@@ -19,7 +19,7 @@ typedef uint16_t bf16_t;   // raw bf16 bit pattern
 // (the contraction index contiguous) for the MFMA kernels; fp32 models: float, [in][out].
 struct LayerWeights {
     void *w_qkv, *w_o, *w_1, *w_2;
-    void *w_1d, *w_2d;           // bf16 models: W_1, W_2 with the contraction index repeated ([out][2 in])
+    void *w_od, *w_1d, *w_2d;    // bf16 models: W_o, W_1, W_2 with the contraction index repeated ([out][2 in])
     float *b_qkv, *b_o, *b_1, *b_2;
     float *ln1_g, *ln1_b, *ln2_g, *ln2_b;
 };
