@@ -17,6 +17,7 @@ SOURCES = ["api.hip", "rowops.hip", "encoder_f32.hip", "encoder_bf16.hip", "gemm
            "anticipate.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+
          "-I", INCLUDE, "-I", CSRC]
 
 
@@ -27,9 +28,14 @@ def _hipcc() -> str:
     return "hipcc"
 
 
+# Per-file additions.  attention: MFMA results go straight to ordinary VGPRs, since the softmax reads
+# every one of them with VALU instructions (the default sends them through the accumulation registers).
+EXTRA_FLAGS = {"attention_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [_hipcc(), *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")

@@ -20,6 +20,8 @@
 //
 // Keys beyond the request's length in the last tile are excluded: their scores are set to -inf
 // before the maximum and their value entries to zero (they may hold anything).
+#include <type_traits>
+
 #include "device_util.h"
 #include "internal.h"
 
@@ -115,13 +117,8 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     float m_run = -INFINITY;      // running maximum of this lane's query (same in both half-waves)
     float l_run = 0.f;            // running sum over the keys this half-wave holds
 
-    const int nkt = (S + BK - 1) / BK;
-    dma_tile(0, 0);
-    for (int kt = 0; kt < nkt; ++kt) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();                                      // tile kt landed; tile kt-1 no longer read
-        if (kt + 1 < nkt) dma_tile((kt + 1) & 1, (kt + 1) * BK);
-        if (!active) continue;
+    auto process_tile = [&](int kt, auto partial_tag) {
+        constexpr bool partial = decltype(partial_tag)::value;
         const unsigned char* sK = smem + (kt & 1) * 2 * TILE_BYTES;
         const unsigned char* sV = sK + TILE_BYTES;
         const int k0 = kt * BK;
@@ -139,7 +136,6 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
             }
         }
         // element e of block b is key k0 + 32 b + 16 (e / 8) + 8 half + 4 ((e / 4) % 2) + e % 4
-        const bool partial = k0 + BK > S;                     // uniform
         if (partial) {
 #pragma unroll
             for (int b = 0; b < 2; ++b)
@@ -203,6 +199,18 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
                     o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[b][j].v, o[i], 0, 0, 0);
                 }
             }
+    };
+
+    const int nkt = (S + BK - 1) / BK;
+    dma_tile(0, 0);
+    for (int kt = 0; kt < nkt; ++kt) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();                                      // tile kt landed; tile kt-1 no longer read
+        if (kt + 1 < nkt) dma_tile((kt + 1) & 1, (kt + 1) * BK);
+        if (!active) continue;
+        // the last tile of a request may be ragged; full tiles run the code without any masking
+        if ((kt + 1) * BK > S) process_tile(kt, std::true_type{});
+        else process_tile(kt, std::false_type{});
     }
     if (!active) return;
 
