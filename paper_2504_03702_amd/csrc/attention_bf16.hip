@@ -3,7 +3,7 @@
 //
 // One workgroup handles 128 consecutive query rows of one request and one head; each of its four
 // wavefronts owns 32 of them.  Keys and values are streamed in tiles of 64 keys through LDS
-// (global_load_lds, double buffered) and shared by the four wavefronts.  Everything is computed
+// (global_load_lds, three stages) and shared by the four wavefronts.  Everything is computed
 // transposed so that a query is a column, i.e. a lane:
 //     S^T[key, q] = K[key, :] . Q[q, :]          (v_mfma_f32_32x32x16_bf16, A = K tile, B = Q^T)
 //     O^T[d, q]  += V^T[d, key] . P^T[key, q]    (A = V^T tile, B = P^T taken from the S^T registers)
@@ -42,6 +42,7 @@ union Frag8 {
 
 constexpr int BK = 64;                 // keys per tile
 constexpr int TILE_BYTES = BK * 128;   // K tile [64 keys][64 d] or V^T tile [64 d][64 keys]
+constexpr int STAGES = 3;              // key/value tiles in LDS: one in use, two on their way
 constexpr float LOG2E = 1.4426950408889634f;
 
 __global__ __launch_bounds__(256) void attention_bf16_kernel(
@@ -52,7 +53,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     int H, int64_t vt_ld, int n_req, const BatchMeta* __restrict__ meta,
     const int32_t* __restrict__ seq_len, const int32_t* __restrict__ row_start,
     const int32_t* __restrict__ qtile_start) {
-    __shared__ __align__(1024) unsigned char smem[2 * 2 * TILE_BYTES];   // 2 stages x (K, V^T)
+    __shared__ __align__(1024) unsigned char smem[STAGES * 2 * TILE_BYTES];   // stages x (K, V^T)
 
     const int qt = blockIdx.x, head = blockIdx.y;
     if (qt >= meta->total_qtiles) return;
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 
     auto process_tile = [&](int kt, auto partial_tag) {
         constexpr bool partial = decltype(partial_tag)::value;
-        const unsigned char* sK = smem + (kt & 1) * 2 * TILE_BYTES;
+        const unsigned char* sK = smem + (kt % STAGES) * 2 * TILE_BYTES;
         const unsigned char* sV = sK + TILE_BYTES;
         const int k0 = kt * BK;
 
@@ -202,11 +203,16 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     };
 
     const int nkt = (S + BK - 1) / BK;
+    // Tile kt + 2 is requested while tile kt is worked on, so a DMA has two tile times to land.  The
+    // memory counter is in order: with the 4 DMA instructions of the newest tile allowed to be
+    // outstanding, everything older has arrived.
     dma_tile(0, 0);
+    if (nkt > 1) dma_tile(1, BK);
     for (int kt = 0; kt < nkt; ++kt) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (kt + 1 < nkt) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();                                      // tile kt landed; tile kt-1 no longer read
-        if (kt + 1 < nkt) dma_tile((kt + 1) & 1, (kt + 1) * BK);
+        if (kt + 2 < nkt) dma_tile((kt + 2) % STAGES, (kt + 2) * BK);
         if (!active) continue;
         // the last tile of a request may be ragged; full tiles run the code without any masking
         if ((kt + 1) * BK > S) process_tile(kt, std::true_type{});
