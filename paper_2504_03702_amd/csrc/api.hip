@@ -82,7 +82,7 @@ Workspace plan_workspace(const ps_model_info& info, int64_t n_tokens, int32_t n_
     memset(&ws, 0, sizeof(ws));
     const size_t es = info.dtype == 1 ? 2 : 4;
     const int64_t H = info.hidden, F = info.ffn;
-    int64_t rows = n_tokens + (int64_t)n_req * (info.n_soft + PS_ROW_ALIGN - 1);
+    int64_t rows = n_tokens + (int64_t)n_req * (info.n_soft + PS_ROW_ALIGN - 1) + PS_KEY_SLACK;
     rows = (int64_t)align_up((size_t)(rows > 0 ? rows : 1), PS_ROW_TILE);
     ws.max_rows = rows;
     ws.max_qtiles = rows / PS_ATT_BQ + n_req;
@@ -364,7 +364,7 @@ extern "C" int ps_model_get_info(const ps_model* m, ps_model_info* out) {
 
 extern "C" size_t ps_workspace_bytes(const ps_model* m, int64_t max_tokens, int32_t max_req) {
     if (!m || max_tokens < 0 || max_req < 0) return 0;
-    if (max_tokens + (int64_t)max_req * (m->info.n_soft + PS_ROW_ALIGN) > (int64_t)0x7fffff00) return 0;
+    if (max_tokens + (int64_t)max_req * (m->info.n_soft + PS_ROW_ALIGN) > (int64_t)0x7ffff000) return 0;
     return plan_workspace(m->info, max_tokens, max_req, nullptr).bytes;
 }
 
@@ -376,7 +376,7 @@ extern "C" int ps_predict_load(ps_model* m, const int32_t* token_ids, const int3
     if (n_req == 0) return PS_OK;
     if (!offsets || !pred_f || !pred_tokens || !workspace || (n_tokens > 0 && !token_ids)) return PS_EINVAL;
     // activation row indices are 32-bit
-    if (n_tokens + (int64_t)n_req * (m->info.n_soft + PS_ROW_ALIGN) > (int64_t)0x7fffff00) return PS_EUNSUPPORTED;
+    if (n_tokens + (int64_t)n_req * (m->info.n_soft + PS_ROW_ALIGN) > (int64_t)0x7ffff000) return PS_EUNSUPPORTED;
     if (((uintptr_t)workspace & 255) != 0) return PS_EWORKSPACE;
     Workspace ws = plan_workspace(m->info, n_tokens, n_req, workspace);
     if (ws.bytes > workspace_bytes) return PS_EWORKSPACE;

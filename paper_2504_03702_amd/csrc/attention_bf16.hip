@@ -19,7 +19,9 @@
 // that the QKV projection's epilogue writes.
 //
 // Keys beyond the request's length in the last tile are excluded: their scores are set to -inf
-// before the maximum and their value entries to zero (they may hold anything).
+// before the maximum, so their weights are exactly zero.  The value rows they multiply only have to
+// be finite: the rows up to PS_KEY_SLACK past the last request are written by the same call's QKV
+// projection (from zero-filled inputs) for that reason.
 #include <type_traits>
 
 #include "device_util.h"
@@ -193,16 +195,6 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
                 for (int i = 0; i < 2; ++i) {
                     Frag8 vf;
                     vf.v = *(const bf16x8*)(sV + i * 4096 + voff[2 * b + j]);
-                    if (partial) {
-                        // zero the value entries of keys beyond the request (they may hold anything)
-                        const int key = k0 + 32 * b + 16 * j + 8 * half;
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) {
-                            uint32_t w = vf.u[t];
-                            if (key + 2 * t >= S) w = 0; else if (key + 2 * t + 1 >= S) w &= 0xffffu;
-                            vf.u[t] = w;
-                        }
-                    }
                     o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[b][j].v, o[i], 0, 0, 0);
                 }
                 lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones.v, pf[b][j].v, lsum, 0, 0, 0);
@@ -250,6 +242,15 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
                     *(uint2*)(c + H) = make_uint2(cvt_pk_bf16(r0, r1), cvt_pk_bf16(r2, r3));
                 }
             }
+    } else if (wq0 + col < ((S + PS_ROW_ALIGN - 1) & ~(PS_ROW_ALIGN - 1))) {
+        // alignment rows between this request and the next: nobody reads their results, but the layers
+        // after this one carry them along and the next layer's key tiles load them, so they must stay
+        // finite.  Zeros here keep every later tensor of these rows finite.
+        bf16_t* orow = out + (int64_t)my_q * H + head * 64;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) *(uint2*)(orow + 32 * i + 8 * e4 + 4 * half) = make_uint2(0u, 0u);
     }
 }
 

@@ -71,7 +71,8 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
     const int H = f.hidden, F = f.ffn;
     bf16_t *x = (bf16_t*)ws.x, *qk = (bf16_t*)ws.qkv, *vt = (bf16_t*)ws.vt, *att = (bf16_t*)ws.att,
            *x1 = (bf16_t*)ws.x1, *g = (bf16_t*)ws.g;
-    const int32_t* rows = &ws.meta->total_rows;
+    const int32_t* rows = &ws.meta->total_rows;        // the rows that belong to requests
+    const int32_t* qkv_rows = &ws.meta->qkv_rows;     // QKV projection: those plus the slack the key tiles read
     const ResidualSrc none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     const int32_t* n_req_dev = &ws.meta->n_req;
     // the stream entering layer 0 is the embedding LayerNorm of the sums the embed kernel left in ya
@@ -83,7 +84,7 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
         const ResidualSrc mid = {ws.yb, ws.sb, w.ln1_g, w.ln1_b, nullptr, nullptr};
         const ResidualSrc mid_cls = {ws.yb, ws.sb, w.ln1_g, w.ln1_b, ws.row_start, ws.seq_len};
         PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_QKV, x, (const bf16_t*)w.w_qkv, w.b_qkv, none, qk, vt,
-                                               ws.max_rows, 3 * H, H, H, rows, s));
+                                               ws.max_rows, 3 * H, H, H, qkv_rows, s));
         PS_TIMED(PS_FAM_ATTENTION, launch_attention_bf16(m, n_req, ws, s));
         PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, att, (const bf16_t*)w.w_o, w.b_o, in, ws.yb,
                                                nullptr, ws.max_rows, H, H, H, rows, s));

@@ -14,6 +14,9 @@ typedef uint16_t bf16_t;   // raw bf16 bit pattern
 #define PS_ROW_ALIGN   8     // every request starts at a multiple of this many activation rows
 #define PS_ROW_TILE    256   // activation buffers are padded to a multiple of this many rows
 #define PS_ATT_BQ      128   // query rows per attention workgroup (bf16 path)
+#define PS_KEY_SLACK   64    // the last key tile of a request reads up to this many rows past its end: they
+                             // must hold finite numbers (their weights are exactly zero), so the embedding
+                             // zero-fills and the GEMMs cover that many rows beyond the last request
 
 // Device weights of one encoder layer.  bf16 models: matrices are bf16, stored [out][in]
 // (the contraction index contiguous) for the MFMA kernels; fp32 models: float, [in][out].
@@ -53,7 +56,7 @@ struct BatchMeta {
     int32_t total_rows;          // activation rows in use (padded request starts included)
     int32_t total_qtiles;        // attention query tiles over all requests
     int32_t n_req;               // requests in this call (row count of the per-request side GEMMs)
-    int32_t pad;
+    int32_t qkv_rows;            // total_rows + PS_KEY_SLACK: rows the QKV projection covers
 };
 
 // Carved-up workspace of one ps_predict_load call.

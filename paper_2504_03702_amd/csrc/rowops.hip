@@ -60,6 +60,7 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ 
         meta->total_rows = s_rows[1023];
         meta->total_qtiles = s_tiles[1023];
         meta->n_req = n_req;
+        meta->qkv_rows = s_rows[1023] + PS_KEY_SLACK;
     }
 }
 
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int total = meta->total_rows;
-    const int64_t live = ((int64_t)total + PS_ROW_TILE - 1) / PS_ROW_TILE * PS_ROW_TILE;
+    const int64_t live = ((int64_t)total + PS_KEY_SLACK + PS_ROW_TILE - 1) / PS_ROW_TILE * PS_ROW_TILE;
     if (row >= live) return;
     T* out = x + row * H;
     float* yrow = y_out ? y_out + row * H : nullptr;     // bf16 path: the fp32 sums and row statistics
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, cons
         float dot = 0.f;
         for (int i = lane; i < H; i += 64) dot += s_c[i] * w[i];
         dot = wave_sum(dot) + b_h1[j];
-        acc += fmaxf(dot, 0.f) * w_h2[j];
+        acc += (dot < 0.f ? 0.f : dot) * w_h2[j];   // ReLU that lets a NaN through to the check below
     }
     if (lane == 0) s_c[H + wave] = acc;
     __syncthreads();
