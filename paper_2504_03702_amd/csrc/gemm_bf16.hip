@@ -18,8 +18,10 @@
 // first k slices of its next tile while the current one finishes, so only the very first tile pays
 // the latency of filling LDS.  The number of rows is only known on the device (padded inputs are
 // compacted); each workgroup derives its tile list from it.  Workgroups are dealt to the 8 XCDs
-// round-robin by the hardware; the tile list is built so that each XCD works on a contiguous run of
-// tiles (n fastest), keeping an A row panel hot in that XCD's L2.
+// round-robin by the hardware; the tile list is built so that the tiles in flight on one XCD are
+// neighbours that share activation row panels and weight column panels through that XCD's L2.
+#include <type_traits>
+
 #include "device_util.h"
 #include "internal.h"
 
@@ -62,21 +64,6 @@ struct Tile {
     static_assert(NW % 2 == 0 && BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile / wave split");
 };
 
-// Bring ROWS x 64 bf16 (rows `ld` elements apart in global memory) into an LDS slice.  `base` is
-// the wave-uniform address of the slice's first row, `lane_off` this lane's byte offset inside the
-// first 8 * NW rows; the uniform part stays in scalar registers so each DMA costs one VGPR.
-template <int ROWS, int NW>
-__device__ __forceinline__ void dma_slice(const unsigned char* base, unsigned lane_off, int64_t ld_bytes,
-                                          unsigned char* lds, int wave) {
-#pragma unroll
-    for (int j = 0; j < ROWS / 8 / NW; ++j) {
-        const unsigned char* ub = base + (int64_t)j * (NW * 8) * ld_bytes;      // wave-uniform: stays in SGPRs
-        const unsigned char* g = ub + lane_off;
-        __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)g, (LDS_AS void*)(lds + (j * NW + wave) * 1024),
-                                         16, 0, 0);
-    }
-}
-
 template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
@@ -97,6 +84,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
     // XCDs round-robin; XCD x works through the contiguous run of tiles [x * per_xcd, (x+1) * per_xcd)
     // (n fastest), its workgroups taking tiles slot, slot + slots, ... of that run, so the tiles in
     // flight on one XCD at any time are neighbours and share A row panels and W column panels in L2.
+    // (Walking 8 x 4 blocks of tiles with the block's weights resident in L2 was measured: no faster.)
     const int rows = *total_rows;
     const int n_tiles = N / BN;
     const int tiles = ((rows + BM - 1) / BM) * n_tiles;
@@ -105,6 +93,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
     const int tile_end = min((xcd + 1) * per_xcd, tiles);
     int tile = xcd * per_xcd + slot;
     if (tile >= tile_end) return;
+    auto tile_origin = [&](int t, int& m0, int& n0) {
+        m0 = (t / n_tiles) * BM;
+        n0 = (t % n_tiles) * BN;
+    };
 
     // ---- DMA sources: lane i of a wavefront fetches chunk (i%8)^swz of row i/8 of its group ----
     const int dma_row = wave * 8 + (lane >> 3);
@@ -150,48 +142,83 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
 #pragma unroll
         for (int j = 0; j < T::TN; ++j) fb[j] = *(const bf16x8*)(sB + j * 4096);
     };
-    auto mfma_step = [&](const bf16x8* fa, const bf16x8* fb) {
-#pragma unroll
-        for (int i = 0; i < T::TM; ++i)
-#pragma unroll
-            for (int j = 0; j < T::TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    };
-    // interleave: a share of the MFMAs, then one LDS read
-    auto interleave = [&]() {
-        constexpr int nR = T::TM + T::TN, nM = T::TM * T::TN;
-#pragma unroll
-        for (int r = 0; r < nM % nR; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x008, nM / nR + 1, 0);     // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // DS read
-        }
-#pragma unroll
-        for (int r = nM % nR; r < nR; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x008, nM / nR, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-    };
-
     const int nk = K / 64;
-    // prefetch cursor: the next slice to fetch is slice pf_kt of tile pf_tile (none once pf_tile >= tile_end)
-    int pf_tile = tile, pf_kt = 0, pf_stage = 0;
-    auto prefetch_next = [&]() {
-        if (pf_tile < tile_end) {
-            const int pm0 = (pf_tile / n_tiles) * BM, pn0 = (pf_tile % n_tiles) * BN;
-            const unsigned char* ga = (const unsigned char*)(A + (int64_t)pm0 * K) + pf_kt * 128;
-            const unsigned char* gw = (const unsigned char*)(W + (int64_t)pn0 * K) + pf_kt * 128;
-            unsigned char* dst = smem + pf_stage * STAGE;
-            dma_slice<BM, T::NW>(ga, lane_off, ld_bytes, dst, wave);
-            dma_slice<BN, T::NW>(gw, lane_off, ld_bytes, dst + T::A_BYTES, wave);
-            pf_stage ^= 1;
-            if (++pf_kt == nk) { pf_kt = 0; pf_tile += slots; }
+    // Prefetch cursor: the next slice to fetch is slice pf_kt of the tile whose operand panels start at
+    // pf_a / pf_w.  Its tile coordinates advance by `slots` tiles without a division.  Once the
+    // workgroup's tiles are used up the cursor parks on the first tile of the problem: the DMAs stay
+    // unconditional (straight-line code the scheduler can interleave with the MFMAs) and the parked
+    // ones refill LDS stages nobody reads any more.
+    const int step_m = slots / n_tiles, step_n = slots % n_tiles;
+    int pf_tile = tile, pf_m = tile / n_tiles, pf_n = tile % n_tiles, pf_kt = 0, pf_stage = 0;
+    const unsigned char* pf_a = (const unsigned char*)(A + (int64_t)pf_m * BM * K);
+    const unsigned char* pf_w = (const unsigned char*)(W + (int64_t)pf_n * BN * K);
+    // The DMA of a slice is issued in two halves, A rows then W rows, each spread among the MFMAs of
+    // one k-step: a wavefront that queues all of a slice's DMA instructions at once waits at the
+    // memory pipeline's issue queue and issues no MFMA meanwhile.
+    auto prefetch_a = [&](int j) {        // DMA j of the slice's A rows
+        const unsigned char* ub = pf_a + pf_kt * 128 + (int64_t)j * (T::NW * 8) * ld_bytes;    // wave-uniform
+        __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)(ub + lane_off),
+                                         (LDS_AS void*)(smem + pf_stage * STAGE + (j * T::NW + wave) * 1024), 16, 0, 0);
+    };
+    auto prefetch_w = [&](int j) {        // DMA j of the slice's W rows
+        const unsigned char* ub = pf_w + pf_kt * 128 + (int64_t)j * (T::NW * 8) * ld_bytes;
+        __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)(ub + lane_off),
+                                         (LDS_AS void*)(smem + pf_stage * STAGE + T::A_BYTES + (j * T::NW + wave) * 1024), 16, 0, 0);
+    };
+    auto advance_cursor = [&]() {         // after the W rows: on to the next slice
+        pf_stage ^= 1;
+        const bool last = ++pf_kt == nk;
+        pf_kt = last ? 0 : pf_kt;
+        pf_tile += last ? slots : 0;
+        int nn = pf_n + (last ? step_n : 0), nm = pf_m + (last ? step_m : 0);
+        const bool wrap = nn >= n_tiles;
+        nn -= wrap ? n_tiles : 0;
+        nm += wrap ? 1 : 0;
+        const bool parked = pf_tile >= tile_end;
+        pf_m = parked ? 0 : nm;
+        pf_n = parked ? 0 : nn;
+        pf_a = (const unsigned char*)(A + (int64_t)pf_m * BM * K);
+        pf_w = (const unsigned char*)(W + (int64_t)pf_n * BN * K);
+    };
+    constexpr int NDMA_A = BM / 8 / T::NW, NDMA_W = BN / 8 / T::NW;
+
+    // One k-step in exact issue order (the scheduler may not move anything across the fences): in
+    // each of TM + TN rounds one fragment read for the next step, at most one DMA, and a share of this
+    // step's MFMAs.  dma_tag: 0 none, 1 the slice's A rows, 2 its W rows.
+    auto k_step = [&](const bf16x8* fa, const bf16x8* fb, bf16x8* na, bf16x8* nb, const unsigned char* rd_stage,
+                      int rd_ks, auto dma_tag) {
+        constexpr int DMA = decltype(dma_tag)::value;
+        constexpr int nR = T::TM + T::TN, nM = T::TM * T::TN;
+        static_assert(NDMA_A <= nR && NDMA_W <= nR, "one DMA per round");
+        const unsigned char* sA = rd_stage + a_off + koff[rd_ks];
+        const unsigned char* sB = rd_stage + T::A_BYTES + b_off + koff[rd_ks];
+#pragma unroll
+        for (int r = 0; r < nR; ++r) {
+            if (r < T::TM) na[r] = *(const bf16x8*)(sA + r * 4096);
+            else nb[r - T::TM] = *(const bf16x8*)(sB + (r - T::TM) * 4096);
+            if (DMA == 1 && r < NDMA_A) prefetch_a(r);
+            if (DMA == 2 && r < NDMA_W) prefetch_w(r);
+            // MFMAs [r * nM / nR, (r + 1) * nM / nR) of the step, in row-major order of the wavefront's tiles
+#pragma unroll
+            for (int m = r * nM / nR; m < (r + 1) * nM / nR; ++m)
+                acc[m / T::TN][m % T::TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m / T::TN], fb[m % T::TN],
+                                                                                   acc[m / T::TN][m % T::TN], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
+    using NoDma = std::integral_constant<int, 0>;
+    using ADma = std::integral_constant<int, 1>;
+    using WDma = std::integral_constant<int, 2>;
 
-    prefetch_next();
+#pragma unroll
+    for (int j = 0; j < NDMA_A; ++j) prefetch_a(j);
+#pragma unroll
+    for (int j = 0; j < NDMA_W; ++j) prefetch_w(j);
+    advance_cursor();
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    prefetch_next();
+#pragma unroll
+    for (int j = 0; j < NDMA_A; ++j) prefetch_a(j);
     read_frags(fa0, fb0, smem, 0);
     int stage = 0;
     float* stg = (float*)(smem + 2 * STAGE + wave * EPI_BYTES);
@@ -203,22 +230,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
             unsigned char* cur = smem + stage * STAGE;
             unsigned char* nxt = smem + (stage ^ 1) * STAGE;
             stage ^= 1;
-            read_frags(fa1, fb1, cur, 1);
-            mfma_step(fa0, fb0);
-            interleave();
-            read_frags(fa0, fb0, cur, 2);
-            mfma_step(fa1, fb1);
-            interleave();
-            read_frags(fa1, fb1, cur, 3);
-            mfma_step(fa0, fb0);
-            interleave();
+            k_step(fa0, fb0, fa1, fb1, cur, 1, WDma{});       // + W half of the slice after this one
+            advance_cursor();
+            k_step(fa1, fb1, fa0, fb0, cur, 2, NoDma{});
+            k_step(fa0, fb0, fa1, fb1, cur, 3, NoDma{});
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            prefetch_next();
-            // step-0 fragments of the next slice (of this tile or of the next one), if there is one
-            if (kt + 1 < nk || tile + slots < tile_end) read_frags(fa0, fb0, nxt, 0);
-            mfma_step(fa1, fb1);
-            interleave();
+            // reads the step-0 fragments of the next slice, of this tile or of the next one (after the
+            // last slice of all: of a stage nobody needs); + A half of the slice two after this one
+            k_step(fa1, fb1, fa0, fb0, nxt, 0, ADma{});
         }
 
         // ---- epilogue -----------------------------------------------------------------------------
@@ -226,7 +246,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
         // + e % 4, col = 32 j + lane % 32: a lane holds one column.  Each wavefront transposes through
         // its private 4 KB of LDS: it writes a strip of accumulators, reads it back with 16 bytes of
         // consecutive output per lane, applies the epilogue there and issues 16-byte global accesses.
-        const int m0 = (tile / n_tiles) * BM, n0 = (tile % n_tiles) * BN;
+        int m0, n0;
+        tile_origin(tile, m0, n0);
         const int m_base = m0 + wm * WTM, n_base = n0 + wn * WTN;
 
         if (EPI == EPI_QKV && n0 >= 2 * hidden) {
@@ -271,36 +292,69 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
         if (EPI == EPI_BIAS_RESIDUAL || EPI == EPI_RESIDUAL_MAPPED) {
             // fp32 sums out: v = acc + bias + LayerNorm(y_prev) recomputed from the row statistics, so
             // the residual stream is never rounded to bf16.  A lane handles 4 consecutive columns.
-            constexpr int LPR = WTN / 4, RPI = 64 / LPR;
+            constexpr int LPR = WTN / 4, RPI = 64 / LPR, NIT = 8 / RPI, NS = 4 * T::TM;
             const int cg = lane % LPR, r_in = lane / LPR;
             const int col = n_base + 4 * cg;
             const float4 bv = *(const float4*)(bias + col);
             const float4 rg = *(const float4*)(res.gamma + col);
             const float4 rb = *(const float4*)(res.beta + col);
             float* Cf = (float*)Cv;
+            auto combine = [&](const float4& a, const float4& yp, const float2& st) {
+                float4 o;
+                o.x = a.x + bv.x + ((yp.x - st.x) * st.y * rg.x + rb.x);
+                o.y = a.y + bv.y + ((yp.y - st.x) * st.y * rg.y + rb.y);
+                o.z = a.z + bv.z + ((yp.z - st.x) * st.y * rg.z + rb.z);
+                o.w = a.w + bv.w + ((yp.w - st.x) * st.y * rg.w + rb.w);
+                return o;
+            };
+            if (EPI == EPI_BIAS_RESIDUAL) {
+                // The previous sums and statistics of strip s + D are requested before strip s is worked
+                // on, so the strips do not each wait out a trip to memory.  Strip s covers rows
+                // 8 s .. 8 s + 7 of the wavefront's tile.
+                constexpr int D = 3;
+                const int64_t row0 = m_base + r_in;
+                const float* yb = res.y + row0 * N + col;
+                const float2* sb = res.stats + row0;
+                float4 yp[D + 1][NIT];
+                float2 st[D + 1][NIT];
+                auto fetch = [&](int s) {
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it) {
+                        yp[s % (D + 1)][it] = *(const float4*)(yb + (int64_t)(8 * s + RPI * it) * N);
+                        st[s % (D + 1)][it] = sb[8 * s + RPI * it];
+                    }
+                };
+#pragma unroll
+                for (int s = 0; s < D; ++s) fetch(s);
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    if (s + D < NS) fetch(s + D);
+                    stage_strip(s / 4, s % 4);
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it) {
+                        const int r = r_in + RPI * it;
+                        const float4 a = *(const float4*)(stg + r * SW + 4 * cg);
+                        *(float4*)(Cf + (row0 + 8 * s + RPI * it) * N + col) =
+                            combine(a, yp[s % (D + 1)][it], st[s % (D + 1)][it]);
+                    }
+                }
+                continue;
+            }
+            // rows mapped through the request table (a small side problem: no prefetch)
 #pragma unroll
             for (int i = 0; i < T::TM; ++i)
 #pragma unroll
                 for (int e4 = 0; e4 < 4; ++e4) {
                     stage_strip(i, e4);
 #pragma unroll
-                    for (int it = 0; it < 8 / RPI; ++it) {
+                    for (int it = 0; it < NIT; ++it) {
                         const int r = r_in + RPI * it;
                         int64_t row = m_base + 32 * i + 8 * e4 + r;
                         const float4 a = *(const float4*)(stg + r * SW + 4 * cg);
-                        if (EPI == EPI_RESIDUAL_MAPPED) {
-                            // GEMM row = request; its stream row is the request's first row
-                            if (row >= rows || res.seq_len[row] <= 0) continue;
-                            row = res.row_map[row];
-                        }
-                        const float2 st = res.stats[row];
-                        const float4 yp = *(const float4*)(res.y + row * N + col);
-                        float4 o;
-                        o.x = a.x + bv.x + ((yp.x - st.x) * st.y * rg.x + rb.x);
-                        o.y = a.y + bv.y + ((yp.y - st.x) * st.y * rg.y + rb.y);
-                        o.z = a.z + bv.z + ((yp.z - st.x) * st.y * rg.z + rb.z);
-                        o.w = a.w + bv.w + ((yp.w - st.x) * st.y * rg.w + rb.w);
-                        *(float4*)(Cf + row * N + col) = o;
+                        // GEMM row = request; its stream row is the request's first row
+                        if (row >= rows || res.seq_len[row] <= 0) continue;
+                        row = res.row_map[row];
+                        *(float4*)(Cf + row * N + col) = combine(a, *(const float4*)(res.y + row * N + col), res.stats[row]);
                     }
                 }
             continue;
@@ -345,6 +399,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
                 }
         }
     }
+    // parked DMAs may still be in flight: they must land before the workgroup gives up its LDS
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 template <int BM, int BN, int WM, int WN>
