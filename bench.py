@@ -141,6 +141,7 @@ def main() -> int:
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = ps.ps_profile_read(model)
+    core_ghz = ps.ps_profile_clock(model) if cfg.dtype == wl.DTYPE_BF16 else 0.0
     ps.ps_profile_enable(model, False)
     flags, _ = ps.ps_status_read(status)
     if flags:
@@ -170,6 +171,11 @@ def main() -> int:
                            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                            "traffic": None, "launches_per_step": gemm_launches // args.steps,
                            "avg_launch_ms": 1e3 * per_launch_s}
+        if core_ghz > 0:
+            # the core clock the chip sustained inside the last GEMM launch (the published peak assumes
+            # 2.4 GHz): achieved / (peak * clock / 2.4) is the matrix cores' utilisation at that clock
+            out["roofline"]["core_clock_ghz_in_kernel"] = core_ghz
+            out["roofline"]["frac_at_sustained_clock"] = achieved / (PEAK_BF16_TFLOPS * core_ghz / 2.4)
         att_ms = prof["attention"][0]
         if att_ms > 0:
             out["attention_tflops"] = attn_flops * args.steps / (att_ms * 1e-3) / 1e12

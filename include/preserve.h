@@ -151,6 +151,12 @@ int ps_anticipate(const int32_t* pred_tokens, const int32_t* instance_id,
 #define PS_FAM_REFINE    5   /* error-compensated feed-forward pass over the [CLS] rows */
 int ps_profile_enable(ps_model* model, int on);
 int ps_profile_read(ps_model* model, void* hip_stream, double* ms /*host*/, int64_t* launches /*host*/);
+/* Core clock the GPU sustained during the last large GEMM launched while profiling was enabled
+ * (bf16 models): one workgroup of that launch counts core cycles against the device's constant-rate
+ * timer.  Waits for `hip_stream`; *core_ghz (host) is 0 if no such launch has run.  The clock under
+ * matrix-core load is what the achieved rate has to be read against: it sits well below the
+ * nominal peak clock.  Errors: PS_EINVAL, PS_EHIP. */
+int ps_profile_clock(ps_model* model, void* hip_stream, double* core_ghz /*host*/);
 
 /* Wait for `hip_stream` and copy a device ps_status to *out (host). */
 int ps_status_read(const ps_status* status /*device*/, void* hip_stream, ps_status* out /*host*/);

@@ -21,7 +21,7 @@ PS_ST_BAD_TOKEN, PS_ST_BAD_LENGTH, PS_ST_NAN, PS_ST_BAD_RECORD, PS_ST_RANGE = 0x
 
 EXPORTS = ["ps_model_load", "ps_model_free", "ps_model_get_info", "ps_workspace_bytes", "ps_predict_load",
            "ps_anticipate_workspace_bytes", "ps_anticipate", "ps_status_read", "ps_strerror",
-           "ps_profile_enable", "ps_profile_read"]
+           "ps_profile_enable", "ps_profile_read", "ps_profile_clock"]
 PS_FAMILIES = ["embed", "gemm", "attention", "layernorm", "head", "refine"]
 
 
@@ -72,6 +72,8 @@ def load_library() -> ctypes.CDLL:
     lib.ps_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.ps_profile_read.restype = ctypes.c_int
     lib.ps_profile_read.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.ps_profile_clock.restype = ctypes.c_int
+    lib.ps_profile_clock.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.ps_strerror.restype = ctypes.c_char_p
     lib.ps_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -134,6 +136,13 @@ def ps_profile_read(model: Model) -> dict:
     ms, cnt = (ctypes.c_double * n)(), (ctypes.c_int64 * n)()
     _check(load_library().ps_profile_read(model.handle, _stream(), ms, cnt), "ps_profile_read")
     return {f: (float(ms[i]), int(cnt[i])) for i, f in enumerate(PS_FAMILIES)}
+
+
+def ps_profile_clock(model: Model) -> float:
+    """Core clock (GHz) sustained during the last large GEMM launched while profiling was on; 0 if none."""
+    ghz = ctypes.c_double(0.0)
+    _check(load_library().ps_profile_clock(model.handle, _stream(), ctypes.byref(ghz)), "ps_profile_clock")
+    return float(ghz.value)
 
 
 def ps_workspace_bytes(model: Model, max_tokens: int, max_req: int) -> int:

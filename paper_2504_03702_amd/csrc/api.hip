@@ -177,6 +177,7 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
     m->ln_eps = (float)eps;
     m->device = device;
     m->blob = nullptr;
+    m->clk_slot = nullptr;
     int lds = 0;
     if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess) lds = 65536;
     m->lds_max = lds;
@@ -298,6 +299,12 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
         delete m;
         return PS_EHIP;
     }
+    if (hipMalloc((void**)&m->clk_slot, 2 * sizeof(int64_t)) != hipSuccess ||
+        hipMemset(m->clk_slot, 0, 2 * sizeof(int64_t)) != hipSuccess) {
+        (void)hipFree(m->blob);
+        delete m;
+        return PS_ENOMEM;
+    }
     uint8_t* b = (uint8_t*)m->blob;
     m->e_tok = b + o_etok;
     m->e_pos = b + o_epos;
@@ -345,6 +352,19 @@ extern "C" int ps_profile_read(ps_model* m, void* hip_stream, double* ms, int64_
     return rc;
 }
 
+extern "C" int ps_profile_clock(ps_model* m, void* hip_stream, double* core_ghz) {
+    if (!m || !core_ghz) return PS_EINVAL;
+    *core_ghz = 0.0;
+    if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return PS_EHIP;
+    int64_t v[2] = {0, 0};
+    int khz = 0;
+    if (hipMemcpy(v, m->clk_slot, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess ||
+        hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, m->device) != hipSuccess)
+        return PS_EHIP;
+    if (v[1] > 0 && khz > 0) *core_ghz = (double)v[0] / ((double)v[1] / ((double)khz * 1e3)) / 1e9;
+    return PS_OK;
+}
+
 extern "C" void ps_model_free(ps_model* m) {
     if (!m) return;
     for (const ProfRecord& r : m->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
@@ -352,6 +372,7 @@ extern "C" void ps_model_free(ps_model* m) {
     if (m->blob) {
         (void)hipSetDevice(m->device);
         (void)hipFree(m->blob);
+        if (m->clk_slot) (void)hipFree(m->clk_slot);
     }
     delete m;
 }

@@ -68,10 +68,10 @@ template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
     ResidualSrc res, void* __restrict__ Cv, bf16_t* __restrict__ Vt, int64_t vt_ld,
-    int N, int K, int hidden, const int32_t* __restrict__ total_rows) {
+    int N, int K, int hidden, const int32_t* __restrict__ total_rows, int64_t* __restrict__ clk) {
     using T = Tile<BM, BN, WM, WN>;
     constexpr int STAGE = T::A_BYTES + T::B_BYTES;      // an A slice followed by a W slice
-    constexpr int EPI_BYTES = 4096;                     // per-wavefront transpose region of the epilogue
+    constexpr int EPI_BYTES = 32768 / T::NW;            // per-wavefront transpose region of the epilogue
     static_assert(2 * STAGE + T::NW * EPI_BYTES <= 160 * 1024, "LDS budget");
     __shared__ __align__(1024) unsigned char smem[2 * STAGE + T::NW * EPI_BYTES];
 
@@ -93,6 +93,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
     const int tile_end = min((xcd + 1) * per_xcd, tiles);
     int tile = xcd * per_xcd + slot;
     if (tile >= tile_end) return;
+    // clock probe (profiling only): core cycles and constant-rate ticks over this workgroup's life
+    const int64_t clk_c0 = clk ? (int64_t)clock64() : 0, clk_w0 = clk ? (int64_t)wall_clock64() : 0;
     auto tile_origin = [&](int t, int& m0, int& n0) {
         m0 = (t / n_tiles) * BM;
         n0 = (t % n_tiles) * BN;
@@ -362,9 +364,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
 
         {
             // bf16 out (plain, GELU, or the query / key columns of the QKV projection): 8 columns per lane
-            constexpr int LPR = WTN / 8, RPI = 64 / LPR;
-            static_assert(RPI == 8, "one 8-row strip per instruction");
-            const int cg = lane % LPR, r = lane / LPR;
+            constexpr int LPR = WTN / 8, RPI = 64 / LPR, NIT = 8 / RPI;
+            const int cg = lane % LPR, r_in = lane / LPR;
             const int col = n_base + 8 * cg;
             const float4 b0 = *(const float4*)(bias + col), b1 = *(const float4*)(bias + col + 4);
             const int64_t ldc = EPI == EPI_QKV ? 2 * (int64_t)hidden : EPI == EPI_GELU_SPLIT ? 2 * (int64_t)N : (int64_t)N;
@@ -374,46 +375,54 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
 #pragma unroll
                 for (int e4 = 0; e4 < 4; ++e4) {
                     stage_strip(i, e4);
-                    const int64_t row = m_base + 32 * i + 8 * e4 + r;
-                    const float4 lo = *(const float4*)(stg + r * SW + 8 * cg);
-                    const float4 hi = *(const float4*)(stg + r * SW + 8 * cg + 4);
-                    float v[8] = {lo.x + b0.x, lo.y + b0.y, lo.z + b0.z, lo.w + b0.w,
-                                  hi.x + b1.x, hi.y + b1.y, hi.z + b1.z, hi.w + b1.w};
-                    if (EPI == EPI_BIAS_GELU || EPI == EPI_GELU_SPLIT) {
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);
-                    }
-                    const uint4 o = make_uint4(cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3]),
-                                               cvt_pk_bf16(v[4], v[5]), cvt_pk_bf16(v[6], v[7]));
-                    *(uint4*)(C + row * ldc + col) = o;
-                    if (EPI == EPI_GELU_SPLIT) {
-                        // second half of the row: what the first rounding lost, as bf16 again
-                        const uint32_t h[4] = {o.x, o.y, o.z, o.w};
-                        uint32_t l[4];
+                    for (int it = 0; it < NIT; ++it) {
+                        const int r = r_in + RPI * it;
+                        const int64_t row = m_base + 32 * i + 8 * e4 + r;
+                        const float4 lo = *(const float4*)(stg + r * SW + 8 * cg);
+                        const float4 hi = *(const float4*)(stg + r * SW + 8 * cg + 4);
+                        float v[8] = {lo.x + b0.x, lo.y + b0.y, lo.z + b0.z, lo.w + b0.w,
+                                      hi.x + b1.x, hi.y + b1.y, hi.z + b1.z, hi.w + b1.w};
+                        if (EPI == EPI_BIAS_GELU || EPI == EPI_GELU_SPLIT) {
 #pragma unroll
-                        for (int t = 0; t < 4; ++t)
-                            l[t] = cvt_pk_bf16(v[2 * t] - __uint_as_float(h[t] << 16),
-                                               v[2 * t + 1] - __uint_as_float(h[t] & 0xffff0000u));
-                        *(uint4*)(C + row * ldc + N + col) = make_uint4(l[0], l[1], l[2], l[3]);
+                            for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);
+                        }
+                        const uint4 o = make_uint4(cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3]),
+                                                   cvt_pk_bf16(v[4], v[5]), cvt_pk_bf16(v[6], v[7]));
+                        *(uint4*)(C + row * ldc + col) = o;
+                        if (EPI == EPI_GELU_SPLIT) {
+                            // second half of the row: what the first rounding lost, as bf16 again
+                            const uint32_t h[4] = {o.x, o.y, o.z, o.w};
+                            uint32_t l[4];
+#pragma unroll
+                            for (int t = 0; t < 4; ++t)
+                                l[t] = cvt_pk_bf16(v[2 * t] - __uint_as_float(h[t] << 16),
+                                                   v[2 * t + 1] - __uint_as_float(h[t] & 0xffff0000u));
+                            *(uint4*)(C + row * ldc + N + col) = make_uint4(l[0], l[1], l[2], l[3]);
+                        }
                     }
                 }
         }
     }
     // parked DMAs may still be in flight: they must land before the workgroup gives up its LDS
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (clk && blockIdx.x == 0 && threadIdx.x == 0) {
+        clk[0] = (int64_t)clock64() - clk_c0;
+        clk[1] = (int64_t)wall_clock64() - clk_w0;
+    }
 }
 
 template <int BM, int BN, int WM, int WN>
 void launch_cfg(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias, ResidualSrc residual,
                 void* C, bf16_t* vt, int64_t max_rows, int N, int K, int hidden, const int32_t* total_rows,
-                hipStream_t s) {
+                int64_t* clk, hipStream_t s) {
     // persistent: one workgroup per compute unit (fewer if there cannot be that many tiles)
     const int64_t tiles = (max_rows + BM - 1) / BM * (N / BN);
     const int64_t wgs = tiles < 256 ? (tiles + 7) / 8 * 8 : 256;
     const dim3 grid((unsigned)wgs), block(WM * WN * 64);
 #define PS_LAUNCH(E)                                                                                       \
     hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, E>), grid, block, 0, s, A, W, bias, residual, C, vt, \
-                       max_rows, N, K, hidden, total_rows)
+                       max_rows, N, K, hidden, total_rows, clk)
     switch (epi) {
         case EPI_BIAS: PS_LAUNCH(EPI_BIAS); break;
         case EPI_BIAS_GELU: PS_LAUNCH(EPI_BIAS_GELU); break;
@@ -431,6 +440,6 @@ void launch_cfg(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float*
 // max_rows rows with max_rows % 256 == 0, so whole tiles are always in bounds.
 void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias,
                       ResidualSrc residual, void* C, bf16_t* vt, int64_t max_rows, int N, int K,
-                      int hidden, const int32_t* total_rows, hipStream_t s) {
-    launch_cfg<256, 256, 2, 4>(epi, A, W, bias, residual, C, vt, max_rows, N, K, hidden, total_rows, s);
+                      int hidden, const int32_t* total_rows, int64_t* clk, hipStream_t s) {
+    launch_cfg<256, 256, 2, 4>(epi, A, W, bias, residual, C, vt, max_rows, N, K, hidden, total_rows, clk, s);
 }

@@ -41,6 +41,7 @@ struct ps_model {
     float ln_eps;
     int device;
     int lds_max;                 // largest LDS allocation of one workgroup on this device
+    int64_t* clk_slot;           // device: {core cycles, timer ticks} of the last profiled GEMM launch
     void* blob;                  // the one device allocation everything below points into
     size_t blob_bytes;
     void *e_tok, *e_pos, *e_soft;     // embedding tables in the model's dtype, [rows][hidden]
@@ -106,10 +107,11 @@ struct ResidualSrc {
     const int32_t* seq_len;  //                       rows with seq_len[r] <= 0 are not stored
 };
 // C[rows, N] = A[rows, K] * W^T (+ epilogue); W is [N][K]; rows = *total_rows (device).
-// EPI_BIAS_RESIDUAL writes fp32 sums (C is float*); the other epilogues write bf16.
+// EPI_BIAS_RESIDUAL writes fp32 sums (C is float*); the other epilogues write bf16.  clk (device,
+// may be null): workgroup 0 leaves {core clock cycles, constant-rate timer ticks} of its run there.
 void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias,
                       ResidualSrc res, void* C, bf16_t* vt, int64_t max_rows, int N, int K,
-                      int hidden, const int32_t* total_rows, hipStream_t s);
+                      int hidden, const int32_t* total_rows, int64_t* clk, hipStream_t s);
 void launch_cls_gather(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, const float2* stats,
                        const float* gamma, const float* beta, hipStream_t s);
 void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s);
