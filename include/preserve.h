@@ -84,7 +84,8 @@ void ps_model_free(ps_model* model);
 int ps_model_get_info(const ps_model* model, ps_model_info* out /*host*/);
 
 /* Bytes of device workspace ps_predict_load() needs for calls with at most `max_tokens` token
- * slots (n_tokens below) and `max_req` requests.  0 on invalid arguments. */
+ * slots (n_tokens below) and `max_req` requests.  0 on invalid arguments or a size ps_predict_load()
+ * refuses. */
 size_t ps_workspace_bytes(const ps_model* model, int64_t max_tokens, int32_t max_req);
 
 /* Predict the response length of n_req requests (Sec. 3.3).
@@ -103,7 +104,9 @@ size_t ps_workspace_bytes(const ps_model* model, int64_t max_tokens, int32_t max
  *   status      device ps_status or NULL; see above.  A request with a fault gets NaN / -1 and
  *               does not disturb the others.
  * Every request is processed with the model's n_soft learnable prompt rows appended after its
- * text tokens.  n_req == 0 is allowed and does nothing. */
+ * text tokens.  n_req == 0 is allowed and does nothing.
+ * Errors: PS_EINVAL (null pointers, negative sizes), PS_EWORKSPACE (too small or misaligned),
+ * PS_EUNSUPPORTED (n_tokens + n_req * (n_soft + 8) above 2^27 activation rows), PS_EHIP. */
 int ps_predict_load(ps_model* model, const int32_t* token_ids, const int32_t* offsets,
                     const int32_t* lengths, int32_t n_req, int64_t n_tokens,
                     float* pred_f, int32_t* pred_tokens,

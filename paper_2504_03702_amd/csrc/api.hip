@@ -385,7 +385,7 @@ extern "C" int ps_model_get_info(const ps_model* m, ps_model_info* out) {
 
 extern "C" size_t ps_workspace_bytes(const ps_model* m, int64_t max_tokens, int32_t max_req) {
     if (!m || max_tokens < 0 || max_req < 0) return 0;
-    if (max_tokens + (int64_t)max_req * (m->info.n_soft + PS_ROW_ALIGN) > (int64_t)0x7ffff000) return 0;
+    if (max_tokens + (int64_t)max_req * (m->info.n_soft + PS_ROW_ALIGN) > PS_MAX_ROWS) return 0;
     return plan_workspace(m->info, max_tokens, max_req, nullptr).bytes;
 }
 
@@ -396,8 +396,8 @@ extern "C" int ps_predict_load(ps_model* m, const int32_t* token_ids, const int3
     if (!m || n_req < 0 || n_tokens < 0) return PS_EINVAL;
     if (n_req == 0) return PS_OK;
     if (!offsets || !pred_f || !pred_tokens || !workspace || (n_tokens > 0 && !token_ids)) return PS_EINVAL;
-    // activation row indices are 32-bit
-    if (n_tokens + (int64_t)n_req * (m->info.n_soft + PS_ROW_ALIGN) > (int64_t)0x7ffff000) return PS_EUNSUPPORTED;
+    // activation row indices are 32-bit and 8 rows of the transposed values span a 32-bit byte offset
+    if (n_tokens + (int64_t)n_req * (m->info.n_soft + PS_ROW_ALIGN) > PS_MAX_ROWS) return PS_EUNSUPPORTED;
     if (((uintptr_t)workspace & 255) != 0) return PS_EWORKSPACE;
     Workspace ws = plan_workspace(m->info, n_tokens, n_req, workspace);
     if (ws.bytes > workspace_bytes) return PS_EWORKSPACE;

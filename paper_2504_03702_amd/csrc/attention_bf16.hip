@@ -46,6 +46,7 @@ constexpr int BK = 64;                 // keys per tile
 constexpr int TILE_BYTES = BK * 128;   // K tile [64 keys][64 d] or V^T tile [64 d][64 keys]
 constexpr int STAGES = 3;              // key/value tiles in LDS: one in use, two on their way
 constexpr float LOG2E = 1.4426950408889634f;
+constexpr float RESCALE_SLACK = 5.5f;  // e^5.5 = 245: how far a score may exceed the exponent's reference
 
 __global__ __launch_bounds__(256) void attention_bf16_kernel(
     const bf16_t* __restrict__ qk,      // [rows][2H]: query columns then key columns
@@ -82,21 +83,37 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     for (int ks = 0; ks < 4; ++ks) qf[ks] = *(const bf16x8*)(qrow + (2 * ks + half) * 8);
 
     // ---- DMA addressing: 2 instructions per wavefront per tile for K, 2 for V^T ------------------
+    // Each address is a wave-uniform base (scalar registers, advanced per tile) plus a per-lane byte
+    // offset that never changes, so a tile's four DMAs cost no vector arithmetic.  Key rows past the
+    // end of the request are loaded as they are (the next request's rows or the slack rows at the end
+    // of the buffer, all inside it): their scores are replaced, not multiplied, by the mask.
     const int drow = lane >> 3;                               // row within an 8-row group
-    auto dma_tile = [&](int stage, int k0) {
+    unsigned k_off[2], v_off[2];                              // per-lane byte offsets
+    const unsigned char *k_base[2], *v_base[2];               // wave-uniform, tile 0
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int grp = j * 4 + wave;
+        const int r = grp * 8 + drow;                         // key row (K tile) / feature row (V^T tile)
+        const int c = (lane & 7) ^ lds_swz(r);
+        // LDS row r of the K tile holds the key with bits 2 and 3 of r swapped (see below)
+        const int kr = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);
+        const int kb = (grp * 8) & ~8;                        // wave-uniform; kr - kb is in 0..15
+        k_off[j] = (unsigned)((kr - kb) * (int)ld_qk + c * 8) * 2u;
+        v_off[j] = (unsigned)(drow * vt_ld + c * 8) * 2u;                      // vt_ld < 2^28 (checked by the host)
+        k_base[j] = (const unsigned char*)(qk + (int64_t)(base + kb) * ld_qk + H + head * 64);
+        v_base[j] = (const unsigned char*)(vt + (int64_t)(head * 64 + grp * 8) * vt_ld + base);
+    }
+    const int64_t k_step = (int64_t)BK * ld_qk * 2;          // bytes per key tile: 64 rows of qk / 64 columns of vt
+    auto dma_tile = [&](int stage, int kt) {
         unsigned char* sK = smem + stage * 2 * TILE_BYTES;
         unsigned char* sV = sK + TILE_BYTES;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int grp = j * 4 + wave;
-            const int r = grp * 8 + drow;                     // key row (K tile) / feature row (V^T tile)
-            const int c = (lane & 7) ^ lds_swz(r);
-            // LDS row r of the K tile holds the key with bits 2 and 3 of r swapped (see below)
-            const int kr = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);
-            const bf16_t* gk = qk + (int64_t)min(base + k0 + kr, last_row) * ld_qk + H + head * 64 + c * 8;
-            __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)gk, (LDS_AS void*)(sK + grp * 1024), 16, 0, 0);
-            const bf16_t* gv = vt + (int64_t)(head * 64 + r) * vt_ld + base + k0 + c * 8;
-            __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)gv, (LDS_AS void*)(sV + grp * 1024), 16, 0, 0);
+            const unsigned char* gk = k_base[j] + kt * k_step;            // wave-uniform
+            const unsigned char* gv = v_base[j] + kt * (BK * 2);
+            __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)(gk + k_off[j]), (LDS_AS void*)(sK + grp * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const GLOBAL_AS void*)(gv + v_off[j]), (LDS_AS void*)(sV + grp * 1024), 16, 0, 0);
         }
     };
 
@@ -160,11 +177,25 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[b][e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);                 // finite: every tile holds a valid key
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * LOG2E);
-        const float mb = m_new * LOG2E;
-        m_run = m_new;
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));               // finite: every tile holds a valid key
+        // The exponent's reference m_run follows the running maximum lazily: it moves only when a tile's
+        // maximum exceeds it by more than RESCALE_SLACK, so weights may reach e^RESCALE_SLACK instead of
+        // 1 (harmless in bf16 and fp32) and the accumulators are rescaled a few times per request
+        // instead of at nearly every tile.  The first tile sets the reference; nothing to rescale yet.
+        if (kt == 0) {
+            m_run = mx;
+        } else if (__any(mx > m_run + RESCALE_SLACK)) {
+            const float m_new = mx > m_run + RESCALE_SLACK ? mx : m_run;
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * LOG2E);
+            m_run = m_new;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) lsum[e] *= alpha;
+        }
+        const float mb = m_run * LOG2E;
         Frag8 pf[2][2];                                       // P^T fragments: [key block][16-key step]
 #pragma unroll
         for (int b = 0; b < 2; ++b)
@@ -176,15 +207,6 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
                     const float p1 = __builtin_amdgcn_exp2f(fmaf(s[b][8 * j + 2 * t + 1], LOG2E, -mb));
                     pf[b][j].u[t] = cvt_pk_bf16(p0, p1);
                 }
-        if (__any(alpha != 1.0f)) {       // once the maxima have settled the accumulators need no rescale
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) lsum[e] *= alpha;
-        }
-
         // O^T += V^T P^T.  Step (b, j) contracts keys 32 b + 16 j + 8 half + 0..7 in this lane, the keys
         // its P fragment holds in that order: the value fragment is key chunk 4 b + 2 j + half.
 #pragma unroll
@@ -206,12 +228,12 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     // memory counter is in order: with the 4 DMA instructions of the newest tile allowed to be
     // outstanding, everything older has arrived.
     dma_tile(0, 0);
-    if (nkt > 1) dma_tile(1, BK);
+    if (nkt > 1) dma_tile(1, 1);
     for (int kt = 0; kt < nkt; ++kt) {
         if (kt + 1 < nkt) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();                                      // tile kt landed; tile kt-1 no longer read
-        if (kt + 2 < nkt) dma_tile((kt + 2) % STAGES, (kt + 2) * BK);
+        if (kt + 2 < nkt) dma_tile((kt + 2) % STAGES, kt + 2);
         if (!active) continue;
         // the last tile of a request may be ragged; full tiles run the code without any masking
         if ((kt + 1) * BK > S) process_tile(kt, std::true_type{});

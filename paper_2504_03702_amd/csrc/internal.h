@@ -14,6 +14,7 @@ typedef uint16_t bf16_t;   // raw bf16 bit pattern
 #define PS_ROW_ALIGN   8     // every request starts at a multiple of this many activation rows
 #define PS_ROW_TILE    256   // activation buffers are padded to a multiple of this many rows
 #define PS_ATT_BQ      128   // query rows per attention workgroup (bf16 path)
+#define PS_MAX_ROWS    ((int64_t)1 << 27)   // most activation rows one call may need (tokens + requests * (M + 8))
 #define PS_KEY_SLACK   64    // the last key tile of a request reads up to this many rows past its end: they
                              // must hold finite numbers (their weights are exactly zero), so the embedding
                              // zero-fills and the GEMMs cover that many rows beyond the last request
