@@ -25,6 +25,26 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 
+# Bytes that left the L2 caches per GEMM launch (average over the four launches of a layer, production
+# workload), from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; profiles/production_gemm_traffic.txt)
+# scaled by what the same counters read for a 1 GiB elementwise copy (x2.0 and x1.0).  Valid only for
+# the kernel source it was measured on: reported as null once that file has changed.
+GEMM_TRAFFIC = {"source_sha256_16": "0c06c2a149b66121", "workload": "production",
+                "fetch_bytes": 33.394e9, "write_bytes": 10.007e9}
+
+
+def measured_gemm_traffic(workload: str):
+    import hashlib
+    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2504_03702_amd", "csrc", "gemm_bf16.hip")
+    try:
+        with open(src, "rb") as f:
+            digest = hashlib.sha256(f.read()).hexdigest()[:16]
+    except OSError:
+        return None
+    if digest != GEMM_TRAFFIC["source_sha256_16"] or workload != GEMM_TRAFFIC["workload"]:
+        return None
+    return GEMM_TRAFFIC["fetch_bytes"] + GEMM_TRAFFIC["write_bytes"]
+
 # workload name -> (encoder shape, prompt recipe, anticipator recipe, description)
 WORKLOADS = {
     "tiny": ("tiny", "tiny", "tiny", "2-layer H128 fp32 encoder, 16 prompts of 8-64 tokens; anticipator 4x64"),
@@ -86,6 +106,8 @@ def main() -> int:
     ap.add_argument("--stream-records", type=int, default=44_100_000,
                     help="records of the anticipator bandwidth stream (0 = skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="also run one plain elementwise copy of this many MiB (a known traffic for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
@@ -100,6 +122,14 @@ def main() -> int:
         return 1
     ps.load_library()
     dev = torch.device("cuda:0")
+    if args.copy_calibration > 0:
+        # reads and writes exactly copy_calibration MiB: what FETCH_SIZE / WRITE_SIZE report for this
+        # kernel scales the same counters of the other kernels in the run
+        src = torch.ones(args.copy_calibration * 262144, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        torch.mul(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     model_kind, prompt_kind, ant_kind, desc = WORKLOADS[args.workload]
     cfg = wl.MODELS[model_kind].resolved()
 
@@ -169,8 +199,13 @@ def main() -> int:
         achieved = per_launch_flops / per_launch_s / 1e12
         out["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": achieved,
                            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                           "traffic": None, "launches_per_step": gemm_launches // args.steps,
+                           "traffic": measured_gemm_traffic(args.workload), "launches_per_step": gemm_launches // args.steps,
                            "avg_launch_ms": 1e3 * per_launch_s}
+        # algorithmic bytes of the same average launch: activations in, weights once, outputs (and the
+        # fp32 residual sums in and out for the two launches that carry them)
+        H, F, T = cfg.hidden, cfg.ffn, int(lengths.sum())
+        out["roofline"]["algorithmic_bytes"] = (T * (2 * H + 6 * H) + T * (2 * H + 8 * H) + T * (2 * H + 2 * F)
+                                               + T * (2 * F + 8 * H) + 2 * (4 * H * H + 2 * H * F)) / 4
         if core_ghz > 0:
             # the core clock the chip sustained inside the last GEMM launch (the published peak assumes
             # 2.4 GHz): achieved / (peak * clock / 2.4) is the matrix cores' utilisation at that clock

@@ -58,7 +58,11 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     const int32_t* __restrict__ qtile_start) {
     __shared__ __align__(1024) unsigned char smem[STAGES * 2 * TILE_BYTES];   // stages x (K, V^T)
 
-    const int qt = blockIdx.x, head = blockIdx.y;
+    // heads vary fastest over the workgroups: the hardware deals consecutive workgroups to the 8 XCDs in
+    // turn, so with 8 | heads all query tiles of one (request, head) run on one XCD and share that
+    // request's keys and values through its L2 instead of fetching them once per XCD
+    const int heads = H / 64;
+    const int head = blockIdx.x % heads, qt = blockIdx.x / heads;
     if (qt >= meta->total_qtiles) return;
     int lo = 0, hi = n_req - 1;          // request of this query tile: largest r with qtile_start[r] <= qt
     while (lo < hi) {
@@ -279,7 +283,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 }  // namespace
 
 void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s) {
-    const dim3 grid((unsigned)ws.max_qtiles, (unsigned)m->info.heads);
+    const dim3 grid((unsigned)(m->info.heads * ws.max_qtiles));      // at most 2^27 / 128 * 32 workgroups
     hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16_t*)ws.qkv, (const bf16_t*)ws.vt,
                        (bf16_t*)ws.att, (bf16_t*)ws.cls_a, m->info.hidden, ws.max_rows, n_req, ws.meta, ws.seq_len, ws.row_start,
                        ws.qtile_start);
