@@ -29,8 +29,8 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 # workload), from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; profiles/production_gemm_traffic.txt)
 # scaled by what the same counters read for a 1 GiB elementwise copy (x2.0 and x1.0).  Valid only for
 # the kernel source it was measured on: reported as null once that file has changed.
-GEMM_TRAFFIC = {"source_sha256_16": "0c06c2a149b66121", "workload": "production",
-                "fetch_bytes": 33.394e9, "write_bytes": 10.007e9}
+GEMM_TRAFFIC = {"source_sha256_16": "59f20461511c7941", "workload": "production",
+                "fetch_bytes": 22.574e9, "write_bytes": 10.008e9}
 
 
 def measured_gemm_traffic(workload: str):

@@ -81,24 +81,54 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
 
     // ---- this workgroup's tiles --------------------------------------------------------------
     // The grid is persistent (one workgroup per compute unit).  The hardware deals workgroups to the 8
-    // XCDs round-robin; XCD x works through the contiguous run of tiles [x * per_xcd, (x+1) * per_xcd)
-    // (n fastest), its workgroups taking tiles slot, slot + slots, ... of that run, so the tiles in
-    // flight on one XCD at any time are neighbours and share A row panels and W column panels in L2.
-    // (Walking 8 x 4 blocks of tiles with the block's weights resident in L2 was measured: no faster.)
+    // XCDs round-robin, so workgroup b runs on XCD b % 8 as its slot b / 8.  Each XCD has its own L2:
+    // the tiles in flight on one XCD should share operand panels, and panels should stay there.
+    // A workgroup walks its tiles (tm, tn) by one rule: tn += step_n, tm += step_m, and when tn passes
+    // the last tile column it wraps and tm += wrap_m.  Three walks use it:
+    //  * large problems whose tile columns come in P groups of 4: the 32 workgroups of an XCD form an
+    //    8 x 4 block of tiles, the fewest distinct panels for 32 tiles.
+    //      - P divides 8: XCD x keeps column group x % P for the whole launch, so that group's weights
+    //        (4 x 256 rows of W) stay in its L2, and walks down the row blocks x / P, x / P + 8 / P, ...;
+    //        the P XCDs that need a row block work on it at the same time, so it comes from HBM once
+    //        and from the memory-side cache for the others.
+    //      - otherwise: XCD x takes row blocks x, x + 8, ... and visits the P column groups of each in
+    //        turn (the row block is re-read from the memory-side cache, the weights rotate).
+    //  * anything else (few tile rows, odd column counts, small grids): XCD x works through the contiguous
+    //    run of tiles [x * per_xcd, (x + 1) * per_xcd), n fastest, its workgroups taking every slots-th.
     const int rows = *total_rows;
-    const int n_tiles = N / BN;
-    const int tiles = ((rows + BM - 1) / BM) * n_tiles;
-    const int per_xcd = (tiles + 7) >> 3;
+    const int n_tiles = N / BN, m_tiles = (rows + BM - 1) / BM;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
-    const int tile_end = min((xcd + 1) * per_xcd, tiles);
-    int tile = xcd * per_xcd + slot;
-    if (tile >= tile_end) return;
+    int tm, tn, step_m, step_n, wrap_m, n_my;                // first tile, walk, number of tiles of this workgroup
+    if (slots == 32 && m_tiles >= 64 && (n_tiles & 3) == 0) {
+        const int P = n_tiles >> 2;
+        if ((8 % P) == 0) {
+            tm = (xcd / P) * 8 + (slot >> 2);
+            tn = (xcd % P) * 4 + (slot & 3);
+            step_m = 64 / P; step_n = 0; wrap_m = 0;
+            n_my = tm < m_tiles ? (m_tiles - tm + step_m - 1) / step_m : 0;
+        } else {
+            tm = xcd * 8 + (slot >> 2);
+            tn = slot & 3;
+            step_m = 0; step_n = 4; wrap_m = 64;
+            n_my = tm < m_tiles ? P * ((m_tiles - tm + 63) / 64) : 0;
+        }
+    } else {
+        const int tiles = m_tiles * n_tiles;
+        const int per_xcd = (tiles + 7) >> 3;
+        const int first = xcd * per_xcd + slot, end = min((xcd + 1) * per_xcd, tiles);
+        tm = first / n_tiles; tn = first % n_tiles;
+        step_m = slots / n_tiles; step_n = slots % n_tiles; wrap_m = 1;
+        n_my = first < end ? (end - first + slots - 1) / slots : 0;
+    }
+    if (n_my == 0) return;
+    auto walk = [&](int& m, int& n) {
+        n += step_n; m += step_m;
+        const bool wrap = n >= n_tiles;
+        n -= wrap ? n_tiles : 0;
+        m += wrap ? wrap_m : 0;
+    };
     // clock probe (profiling only): core cycles and constant-rate ticks over this workgroup's life
     const int64_t clk_c0 = clk ? (int64_t)clock64() : 0, clk_w0 = clk ? (int64_t)wall_clock64() : 0;
-    auto tile_origin = [&](int t, int& m0, int& n0) {
-        m0 = (t / n_tiles) * BM;
-        n0 = (t % n_tiles) * BN;
-    };
 
     // ---- DMA sources: lane i of a wavefront fetches chunk (i%8)^swz of row i/8 of its group ----
     const int dma_row = wave * 8 + (lane >> 3);
@@ -145,13 +175,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
         for (int j = 0; j < T::TN; ++j) fb[j] = *(const bf16x8*)(sB + j * 4096);
     };
     const int nk = K / 64;
-    // Prefetch cursor: the next slice to fetch is slice pf_kt of the tile whose operand panels start at
-    // pf_a / pf_w.  Its tile coordinates advance by `slots` tiles without a division.  Once the
-    // workgroup's tiles are used up the cursor parks on the first tile of the problem: the DMAs stay
-    // unconditional (straight-line code the scheduler can interleave with the MFMAs) and the parked
-    // ones refill LDS stages nobody reads any more.
-    const int step_m = slots / n_tiles, step_n = slots % n_tiles;
-    int pf_tile = tile, pf_m = tile / n_tiles, pf_n = tile % n_tiles, pf_kt = 0, pf_stage = 0;
+    // Prefetch cursor: the next slice to fetch is slice pf_kt of tile (pf_m, pf_n), the pf_it-th of this
+    // workgroup.  Once its tiles are used up the cursor parks on the first tile of the problem: the
+    // DMAs stay unconditional (straight-line code the scheduler can interleave with the MFMAs) and the
+    // parked ones refill LDS stages nobody reads any more.
+    int pf_it = 0, pf_m = tm, pf_n = tn, pf_kt = 0, pf_stage = 0;
     const unsigned char* pf_a = (const unsigned char*)(A + (int64_t)pf_m * BM * K);
     const unsigned char* pf_w = (const unsigned char*)(W + (int64_t)pf_n * BN * K);
     // The DMA of a slice is issued in two halves, A rows then W rows, each spread among the MFMAs of
@@ -171,14 +199,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
         pf_stage ^= 1;
         const bool last = ++pf_kt == nk;
         pf_kt = last ? 0 : pf_kt;
-        pf_tile += last ? slots : 0;
-        int nn = pf_n + (last ? step_n : 0), nm = pf_m + (last ? step_m : 0);
-        const bool wrap = nn >= n_tiles;
-        nn -= wrap ? n_tiles : 0;
-        nm += wrap ? 1 : 0;
-        const bool parked = pf_tile >= tile_end;
-        pf_m = parked ? 0 : nm;
-        pf_n = parked ? 0 : nn;
+        pf_it += last ? 1 : 0;
+        int nm = pf_m, nn = pf_n;
+        walk(nm, nn);
+        const bool parked = pf_it >= n_my;
+        pf_m = parked ? 0 : last ? nm : pf_m;
+        pf_n = parked ? 0 : last ? nn : pf_n;
         pf_a = (const unsigned char*)(A + (int64_t)pf_m * BM * K);
         pf_w = (const unsigned char*)(W + (int64_t)pf_n * BN * K);
     };
@@ -226,7 +252,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
     float* stg = (float*)(smem + 2 * STAGE + wave * EPI_BYTES);
     constexpr int WTM = BM / WM, WTN = BN / WN;
 
-    for (; tile < tile_end; tile += slots) {
+    for (int it = 0; it < n_my; ++it, walk(tm, tn)) {
         clear_acc();
         for (int kt = 0; kt < nk; ++kt) {
             unsigned char* cur = smem + stage * STAGE;
@@ -248,8 +274,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
         // + e % 4, col = 32 j + lane % 32: a lane holds one column.  Each wavefront transposes through
         // its private 4 KB of LDS: it writes a strip of accumulators, reads it back with 16 bytes of
         // consecutive output per lane, applies the epilogue there and issues 16-byte global accesses.
-        int m0, n0;
-        tile_origin(tile, m0, n0);
+        const int m0 = tm * BM, n0 = tn * BN;
         const int m_base = m0 + wm * WTM, n_base = n0 + wn * WTN;
 
         if (EPI == EPI_QKV && n0 >= 2 * hidden) {
