@@ -139,6 +139,46 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
         src = e_soft + (int64_t)(p - n_text) * H;
     }
     const T* pos = e_pos + (int64_t)p * H;
+    if (sizeof(T) == 2 && yrow) {
+        // bf16 models (H a multiple of 256, at most 2048): the row stays in registers, lane l holding the
+        // 4-element chunks l, l + 64, ...; 8-byte loads, one pass over the tables
+        const int nch = H >> 8;
+        float4 e[8];
+        float sum = 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            if (c < nch) {
+                const uint2 a = ((const uint2*)src)[lane + 64 * c], b = ((const uint2*)pos)[lane + 64 * c];
+                e[c].x = __uint_as_float(a.x << 16) + __uint_as_float(b.x << 16);
+                e[c].y = __uint_as_float(a.x & 0xffff0000u) + __uint_as_float(b.x & 0xffff0000u);
+                e[c].z = __uint_as_float(a.y << 16) + __uint_as_float(b.y << 16);
+                e[c].w = __uint_as_float(a.y & 0xffff0000u) + __uint_as_float(b.y & 0xffff0000u);
+                sum += (e[c].x + e[c].y) + (e[c].z + e[c].w);
+            }
+        }
+        const float mean = wave_sum(sum) / (float)H;
+        float sq = 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            if (c < nch) {
+                const float dx = e[c].x - mean, dy = e[c].y - mean, dz = e[c].z - mean, dw = e[c].w - mean;
+                sq += (dx * dx + dy * dy) + (dz * dz + dw * dw);
+            }
+        }
+        const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)H + eps);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            if (c < nch) {
+                const float4 g = ((const float4*)gamma)[lane + 64 * c], bt = ((const float4*)beta)[lane + 64 * c];
+                ((float4*)yrow)[lane + 64 * c] = e[c];
+                ((uint2*)out)[lane + 64 * c] =
+                    make_uint2(pack_bf16x2((e[c].x - mean) * rstd * g.x + bt.x, (e[c].y - mean) * rstd * g.y + bt.y),
+                               pack_bf16x2((e[c].z - mean) * rstd * g.z + bt.z, (e[c].w - mean) * rstd * g.w + bt.w));
+            }
+        }
+        if (lane == 0) stats_out[row] = make_float2(mean, rstd);
+        return;
+    }
     float sum = 0.f;
     for (int i = lane; i < H; i += 64) sum += load_elem<T>(src, i) + load_elem<T>(pos, i);
     const float mean = wave_sum(sum) / (float)H;
