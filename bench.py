@@ -61,11 +61,14 @@ WORKLOADS = {
 
 
 def encoder_flops(cfg, lengths):
-    """Algorithmic flops of one call on real tokens: GEMMs and attention separately."""
+    """Flops of the work one call asks of the GEMM and attention kernels, on real tokens.  In the last
+    layer only the first row of every request goes on to the head, so there the library runs the QKV
+    projection alone over all rows and attention for the first rows: that is what is counted (the
+    small per-request side GEMMs are left out)."""
     H, F, L = cfg.hidden, cfg.ffn, cfg.layers
     S = lengths.astype(np.float64) + cfg.n_soft
-    gemm = L * S.sum() * (8.0 * H * H + 4.0 * H * F)
-    attn = L * 4.0 * H * (S ** 2).sum()
+    gemm = (L - 1) * S.sum() * (8.0 * H * H + 4.0 * H * F) + S.sum() * 6.0 * H * H
+    attn = (L - 1) * 4.0 * H * (S ** 2).sum() + 4.0 * H * S.sum()
     return gemm, attn
 
 
@@ -203,9 +206,10 @@ def main() -> int:
                            "avg_launch_ms": 1e3 * per_launch_s}
         # algorithmic bytes of the same average launch: activations in, weights once, outputs (and the
         # fp32 residual sums in and out for the two launches that carry them)
-        H, F, T = cfg.hidden, cfg.ffn, int(lengths.sum())
-        out["roofline"]["algorithmic_bytes"] = (T * (2 * H + 6 * H) + T * (2 * H + 8 * H) + T * (2 * H + 2 * F)
-                                               + T * (2 * F + 8 * H) + 2 * (4 * H * H + 2 * H * F)) / 4
+        H, F, T, L = cfg.hidden, cfg.ffn, int(lengths.sum()), cfg.layers
+        qkv_b = T * (2 * H + 6 * H) + 6 * H * H
+        rest_b = T * (2 * H + 8 * H) + T * (2 * H + 2 * F) + T * (2 * F + 8 * H) + 2 * H * H + 4 * H * F
+        out["roofline"]["algorithmic_bytes"] = (L * qkv_b + (L - 1) * rest_b) / (4 * (L - 1) + 1)
         if core_ghz > 0:
             # the core clock the chip sustained inside the last GEMM launch (the published peak assumes
             # 2.4 GHz): achieved / (peak * clock / 2.4) is the matrix cores' utilisation at that clock

@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     bf16_t* __restrict__ cls_out,       // [requests][2H]: first row of every request as hi | lo bf16 pairs
     int H, int64_t vt_ld, int n_req, const BatchMeta* __restrict__ meta,
     const int32_t* __restrict__ seq_len, const int32_t* __restrict__ row_start,
-    const int32_t* __restrict__ qtile_start) {
+    const int32_t* __restrict__ qtile_start, int first_rows_only) {
     __shared__ __align__(1024) unsigned char smem[STAGES * 2 * TILE_BYTES];   // stages x (K, V^T)
 
     // heads vary fastest over the workgroups: the hardware deals consecutive workgroups to the 8 XCDs in
@@ -72,6 +72,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     const int S = seq_len[lo];
     const int base = row_start[lo];
     const int q0 = (qt - qtile_start[lo]) * PS_ATT_BQ;
+    if (first_rows_only && q0 != 0) return;                 // whole workgroup: nothing to wait for
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, half = lane >> 5;
     const int last_row = base + S - 1;
@@ -79,7 +80,8 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 
     // ---- this wavefront's queries: B operand fragments, one per 16-deep slice of the head -------
     const int wq0 = q0 + 32 * wave;
-    const bool active = wq0 < S;                              // wave-uniform
+    // wave-uniform; inactive wavefronts still move tiles and meet the barriers
+    const bool active = wq0 < S && !(first_rows_only && wave != 0);
     const int my_q = base + wq0 + col;
     const bf16_t* qrow = qk + (int64_t)min(my_q, last_row) * ld_qk + head * 64;
     bf16x8 qf[4];
@@ -282,9 +284,9 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 
 }  // namespace
 
-void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s) {
+void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, bool first_rows_only, hipStream_t s) {
     const dim3 grid((unsigned)(m->info.heads * ws.max_qtiles));      // at most 2^27 / 128 * 32 workgroups
     hipLaunchKernelGGL(attention_bf16_kernel, grid, dim3(256), 0, s, (const bf16_t*)ws.qkv, (const bf16_t*)ws.vt,
                        (bf16_t*)ws.att, (bf16_t*)ws.cls_a, m->info.hidden, ws.max_rows, n_req, ws.meta, ws.seq_len, ws.row_start,
-                       ws.qtile_start);
+                       ws.qtile_start, first_rows_only ? 1 : 0);
 }

@@ -81,25 +81,35 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
 #define PS_TIMED(FAM, CALL) do { ProfScope p_(m, FAM, s); CALL; } while (0)
     for (int l = 0; l < f.layers; ++l) {
         const LayerWeights& w = m->layers[(size_t)l];
+        // After the last layer only the first row of every request goes on (to the head), and within
+        // that layer a row's output projection and feed-forward block depend on no other row: there the
+        // all-row GEMMs and LayerNorms are skipped, attention computes the first rows only, and the
+        // per-request side pass below, which every layer runs for accuracy, is all that is left.
+        const bool last = l + 1 == f.layers;
         const ResidualSrc in = {ws.ya, ws.sa, sg, sbeta, nullptr, nullptr};
         const ResidualSrc mid = {ws.yb, ws.sb, w.ln1_g, w.ln1_b, nullptr, nullptr};
         const ResidualSrc mid_cls = {ws.yb, ws.sb, w.ln1_g, w.ln1_b, ws.row_start, ws.seq_len};
         PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_QKV, x, (const bf16_t*)w.w_qkv, w.b_qkv, none, qk, vt,
                                                ws.max_rows, 3 * H, H, H, qkv_rows, clk, s));
-        PS_TIMED(PS_FAM_ATTENTION, launch_attention_bf16(m, n_req, ws, s));
-        PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, att, (const bf16_t*)w.w_o, w.b_o, in, ws.yb,
-                                               nullptr, ws.max_rows, H, H, H, rows, clk, s));
+        PS_TIMED(PS_FAM_ATTENTION, launch_attention_bf16(m, n_req, ws, last, s));
+        if (!last)
+            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, att, (const bf16_t*)w.w_o, w.b_o, in, ws.yb,
+                                                   nullptr, ws.max_rows, H, H, H, rows, clk, s));
         // output projection again for each request's first row from the hi | lo pairs the attention
         // kernel left in cls_a (see the feed-forward refinement below)
         const ResidualSrc in_cls = {ws.ya, ws.sa, sg, sbeta, ws.row_start, ws.seq_len};
         PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_RESIDUAL_MAPPED, (const bf16_t*)ws.cls_a, (const bf16_t*)w.w_od,
                                                  w.b_o, in_cls, ws.yb, nullptr, ws.cls_rows, H, 2 * H, H, n_req_dev, nullptr, s));
-        PS_TIMED(PS_FAM_LAYERNORM, launch_layernorm_bf16(ws.yb, x1, ws.sb, w.ln1_g, w.ln1_b, m->ln_eps, H,
-                                                         ws.max_rows, rows, s));
-        PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_GELU, x1, (const bf16_t*)w.w_1, w.b_1, none, g, nullptr,
-                                               ws.max_rows, F, H, H, rows, clk, s));
-        PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, g, (const bf16_t*)w.w_2, w.b_2, mid, ws.ya,
-                                               nullptr, ws.max_rows, H, F, H, rows, clk, s));
+        if (!last) {
+            PS_TIMED(PS_FAM_LAYERNORM, launch_layernorm_bf16(ws.yb, x1, ws.sb, w.ln1_g, w.ln1_b, m->ln_eps, H,
+                                                             ws.max_rows, rows, s));
+            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_GELU, x1, (const bf16_t*)w.w_1, w.b_1, none, g, nullptr,
+                                                   ws.max_rows, F, H, H, rows, clk, s));
+            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, g, (const bf16_t*)w.w_2, w.b_2, mid, ws.ya,
+                                                   nullptr, ws.max_rows, H, F, H, rows, clk, s));
+        } else {
+            PS_TIMED(PS_FAM_LAYERNORM, launch_cls_stats(m, n_req, ws, ws.yb, ws.sb, s));
+        }
         // The feed-forward block again for each request's first row, the one the head reads, with its
         // input and its GELU output carried as two bf16 values per element (contraction length doubled,
         // weights repeated): bf16 rounding of these two tensors is the dominant error of the prediction
@@ -109,8 +119,11 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
                                                  none, ws.cls_g, nullptr, ws.cls_rows, F, 2 * H, H, n_req_dev, nullptr, s));
         PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_RESIDUAL_MAPPED, (const bf16_t*)ws.cls_g, (const bf16_t*)w.w_2d,
                                                  w.b_2, mid_cls, ws.ya, nullptr, ws.cls_rows, H, 2 * F, H, n_req_dev, nullptr, s));
-        PS_TIMED(PS_FAM_LAYERNORM, launch_layernorm_bf16(ws.ya, x, ws.sa, w.ln2_g, w.ln2_b, m->ln_eps, H,
-                                                         ws.max_rows, rows, s));
+        if (!last)
+            PS_TIMED(PS_FAM_LAYERNORM, launch_layernorm_bf16(ws.ya, x, ws.sa, w.ln2_g, w.ln2_b, m->ln_eps, H,
+                                                             ws.max_rows, rows, s));
+        else
+            PS_TIMED(PS_FAM_LAYERNORM, launch_cls_stats(m, n_req, ws, ws.ya, ws.sa, s));   // what the head reads
         sg = w.ln2_g;
         sbeta = w.ln2_b;
     }

@@ -115,7 +115,12 @@ void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const 
                       int hidden, const int32_t* total_rows, int64_t* clk, hipStream_t s);
 void launch_cls_gather(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, const float2* stats,
                        const float* gamma, const float* beta, hipStream_t s);
-void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s);
+// stats[first row of request r] = LayerNorm statistics of that row of y, for every request.
+void launch_cls_stats(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, float2* stats,
+                      hipStream_t s);
+// first_rows_only: compute (at least) the first query row of every request and nothing beyond its
+// first 32 rows; the rest of the output buffer keeps its old contents.
+void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, bool first_rows_only, hipStream_t s);
 // x = bf16(LayerNorm(y)) and stats = (mean, 1/std) for every live row of the fp32 sums y.
 void launch_layernorm_bf16(const float* y, bf16_t* x, float2* stats, const float* gamma, const float* beta,
                            float eps, int hidden, int64_t max_rows, const int32_t* total_rows,

@@ -280,7 +280,36 @@ __global__ __launch_bounds__(256) void cls_gather_kernel(const float* __restrict
     }
 }
 
+// LayerNorm statistics (mean, 1 / std; biased variance) of each request's first row of the fp32 sums y:
+// one wavefront per request.  Used where only those rows go on (the last layer), in place of the
+// LayerNorm over all rows.
+__global__ __launch_bounds__(256) void cls_stats_kernel(const float* __restrict__ y, float2* __restrict__ stats, float eps,
+                                                        int H, int n_req, const int32_t* __restrict__ seq_len,
+                                                        const int32_t* __restrict__ row_start) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= n_req || seq_len[r] <= 0) return;
+    const int64_t row = row_start[r];
+    const float* yr = y + row * H;
+    float sum = 0.f;
+    for (int i = lane; i < H; i += 64) sum += yr[i];
+    const float mean = wave_sum(sum) / (float)H;
+    float sq = 0.f;
+    for (int i = lane; i < H; i += 64) {
+        const float d = yr[i] - mean;
+        sq = fmaf(d, d, sq);
+    }
+    const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)H + eps);
+    if (lane == 0) stats[row] = make_float2(mean, rstd);
+}
+
 }  // namespace
+
+void launch_cls_stats(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, float2* stats,
+                      hipStream_t s) {
+    hipLaunchKernelGGL(cls_stats_kernel, dim3((unsigned)(ws.cls_rows / 4)), dim3(256), 0, s, y, stats, m->ln_eps,
+                       m->info.hidden, n_req, ws.seq_len, ws.row_start);
+}
 
 void launch_cls_gather(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, const float2* stats,
                        const float* gamma, const float* beta, hipStream_t s) {
