@@ -54,6 +54,35 @@ def test_small_model_shapes(tmp_models, lengths):
     check(model, ref, batch)
 
 
+def test_single_layer_model(tmp_models):
+    """One layer: the first layer is also the last, where only the requests' first rows go on."""
+    cfg = dataclasses.replace(SMALL, layers=1)
+    model, ref = make(tmp_models, "small_bf16_1layer.bin", cfg, ln_jitter=0.1, bias_std=0.05)
+    lengths = np.array([1, 33, 64, 200, 129, 7], np.int32)
+    ids = np.random.default_rng(5).integers(0, cfg.vocab, int(lengths.sum())).astype(np.int32)
+    check(model, ref, wl.pack_prompts(lengths, ids))
+
+
+def test_profile_hooks(tmp_models):
+    """Kernel-family timing and the clock probe: plausible values, nothing left behind when off."""
+    model, _ = make(tmp_models, "small_bf16.bin", SMALL, ln_jitter=0.1, bias_std=0.05)
+    lengths = np.full(64, 512, np.int32)
+    ids = np.random.default_rng(6).integers(0, SMALL.vocab, int(lengths.sum())).astype(np.int32)
+    batch = wl.pack_prompts(lengths, ids)
+    ps.ps_profile_enable(model, True)
+    ps.ps_profile_read(model)
+    run_predict(model, batch)
+    prof = ps.ps_profile_read(model)
+    ghz = ps.ps_profile_clock(model)
+    ps.ps_profile_enable(model, False)
+    assert set(prof) == set(ps.PS_FAMILIES)
+    assert prof["gemm"][1] == 4 * (SMALL.layers - 1) + 1 and prof["gemm"][0] > 0
+    assert prof["attention"][1] == SMALL.layers and prof["head"][1] == 1
+    assert 0.3 < ghz < 3.0
+    run_predict(model, batch)
+    assert all(v == (0.0, 0) for v in ps.ps_profile_read(model).values())
+
+
 def test_padded_equals_packed_and_learnable_prompts(tmp_models):
     cfg = dataclasses.replace(SMALL, n_soft=5, layers=3)
     model, ref = make(tmp_models, "small_bf16_soft.bin", cfg, ln_jitter=0.1, bias_std=0.05)
