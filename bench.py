@@ -25,12 +25,12 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 
-# Bytes that left the L2 caches per GEMM launch (average over the four launches of a layer, production
-# workload), from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; profiles/production_gemm_traffic.txt)
+# Bytes that left the L2 caches per large-GEMM launch (average over the 61 launches of a production
+# step), from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; profiles/production_gemm_traffic.txt)
 # scaled by what the same counters read for a 1 GiB elementwise copy (x2.0 and x1.0).  Valid only for
 # the kernel source it was measured on: reported as null once that file has changed.
-GEMM_TRAFFIC = {"source_sha256_16": "59f20461511c7941", "workload": "production",
-                "fetch_bytes": 22.574e9, "write_bytes": 10.008e9}
+GEMM_TRAFFIC = {"source_sha256_16": "f42587646c088dd2", "workload": "production",
+                "fetch_bytes": 22.616e9, "write_bytes": 10.023e9}
 
 
 def measured_gemm_traffic(workload: str):

@@ -466,9 +466,10 @@ void launch_cfg(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float*
 void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias,
                       ResidualSrc residual, void* C, bf16_t* vt, int64_t max_rows, int N, int K,
                       int hidden, const int32_t* total_rows, int64_t* clk, hipStream_t s) {
-    // The per-request side problems have few rows (one per request) and long contractions: 128 x 128
-    // tiles give four times as many workgroups to spread them over.
-    if (epi == EPI_GELU_SPLIT || epi == EPI_RESIDUAL_MAPPED)
+    // The per-request side problems that reduce to `hidden` columns have few tiles (one row per request,
+    // few tile columns) and long contractions: 128 x 128 tiles give four times as many workgroups to
+    // spread them over.
+    if (epi == EPI_RESIDUAL_MAPPED)
         launch_cfg<128, 128, 2, 2>(epi, A, W, bias, residual, C, vt, max_rows, N, K, hidden, total_rows, clk, s);
     else
         launch_cfg<256, 256, 2, 4>(epi, A, W, bias, residual, C, vt, max_rows, N, K, hidden, total_rows, clk, s);
