@@ -141,14 +141,10 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[i][e] = 0.f;
     float m_run = -INFINITY;      // running maximum of this lane's query (same in both half-waves)
-    // running sum of the (bf16-rounded) weights of this lane's query, accumulated by the matrix core
-    // as an all-ones row times P^T: every element of the tile holds the same sum
-    f32x16 lsum;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) lsum[e] = 0.f;
-    Frag8 ones;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) ones.u[t] = 0x3f803f80u;
+    // running sum of this lane's share of the weights of its query (the other half-wavefront holds the
+    // other keys; the two are added once, at the end).  Summed in fp32 before the weights are rounded
+    // to bf16 for the second product: the rounding errors of the numerator average out over the keys.
+    float l_run = 0.f;
 
     auto process_tile = [&](int kt, auto partial_tag) {
         constexpr bool partial = decltype(partial_tag)::value;
@@ -198,8 +194,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) lsum[e] *= alpha;
+            l_run *= alpha;
         }
         const float mb = m_run * LOG2E;
         Frag8 pf[2][2];                                       // P^T fragments: [key block][16-key step]
@@ -211,6 +206,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
                 for (int t = 0; t < 4; ++t) {
                     const float p0 = __builtin_amdgcn_exp2f(fmaf(s[b][8 * j + 2 * t], LOG2E, -mb));
                     const float p1 = __builtin_amdgcn_exp2f(fmaf(s[b][8 * j + 2 * t + 1], LOG2E, -mb));
+                    l_run += p0 + p1;
                     pf[b][j].u[t] = cvt_pk_bf16(p0, p1);
                 }
         // O^T += V^T P^T.  Step (b, j) contracts keys 32 b + 16 j + 8 half + 0..7 in this lane, the keys
@@ -225,7 +221,6 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
                     vf.v = *(const bf16x8*)(sV + i * 4096 + voff[2 * b + j]);
                     o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[b][j].v, o[i], 0, 0, 0);
                 }
-                lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones.v, pf[b][j].v, lsum, 0, 0, 0);
             }
     };
 
@@ -248,7 +243,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     if (!active) return;
 
     // ---- normalise and store: element e of block i is feature 32 i + 8 (e / 4) + 4 half + e % 4 -----
-    const float inv = 1.0f / lsum[0];
+    const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32, 64));
     if (wq0 + col < S) {
         bf16_t* orow = out + (int64_t)my_q * H + head * 64;
 #pragma unroll
