@@ -158,9 +158,22 @@ def main() -> int:
     aws = ps.alloc_workspace(ps.ps_anticipate_workspace_bytes(n_req, ant.n_inst, ant.horizon), dev)
     status = ps.new_status(dev)
 
+    # the same batch in the paper's own units: each request admitted into its instance's look-ahead map
+    # with its prompt length and the prediction just made (Sec. 3.4.1)
+    la = wl.make_lookahead_inputs(ant_kind if ant_kind in ("tiny", "production") else "medium", seed=0, n=n_req)
+    la_start = t32(np.random.default_rng(7).integers(0, la.map_len // 4, n_req))
+    la_prompt, la_zero = t32(lengths), torch.zeros(n_req, dtype=torch.int32, device=dev)
+    la_sign = torch.ones(n_req, dtype=torch.int32, device=dev)
+    la_inst = inst % la.n_inst
+    la_kv = torch.zeros(la.n_inst * la.map_len, dtype=torch.int32, device=dev)
+    la_ovf = torch.zeros(la.n_inst, dtype=torch.int64, device=dev)
+    la_ws = ps.alloc_workspace(ps.ps_lookahead_workspace_bytes(la.n_inst, la.map_len), dev)
+
     def step():
         ps.ps_predict_load(model, ids, offs, lens, pred_f, pred_t, ws, status)
         ps.ps_anticipate(pred_t, inst, arr, rate, ant.n_inst, ant.horizon, load, ovf, aws, status)
+        ps.ps_lookahead_update(la_inst, la_start, la_prompt, la_zero, pred_t, la_sign, la.n_inst, la.map_len,
+                               la_kv, la_ovf, la_ws, status=status)
 
     for _ in range(args.warmup):
         step()
@@ -244,6 +257,34 @@ def main() -> int:
         out["anticipator"] = {"bound": "hbm", "records": args.stream_records, "ms_per_call": 1e3 * call_s,
                               "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
                               "records_per_s": args.stream_records / call_s}
+
+    # ---- look-ahead map in KV-token units on a long record stream -----------------------------------
+    if args.stream_records > 0:
+        torch.cuda.empty_cache()
+        n_la = min(args.stream_records, 10_000_000)
+        s_la = wl.make_lookahead_inputs("stream", seed=0, n=n_la)
+        cols = [t32(c) for c in s_la.columns()]
+        n_rec = cols[0].numel()
+        kv = torch.zeros(s_la.n_inst * s_la.map_len, dtype=torch.int32, device=dev)
+        ovf2 = torch.zeros(s_la.n_inst, dtype=torch.int64, device=dev)
+        lws = ps.alloc_workspace(ps.ps_lookahead_workspace_bytes(s_la.n_inst, s_la.map_len), dev)
+        reps = 10
+        for _ in range(2):
+            ps.ps_lookahead_update(*cols, s_la.n_inst, s_la.map_len, kv, ovf2, lws, status=status)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            ps.ps_lookahead_update(*cols, s_la.n_inst, s_la.map_len, kv, ovf2, lws, status=status)
+        e1.record()
+        torch.cuda.synchronize()
+        call_s = e0.elapsed_time(e1) * 1e-3 / reps
+        # algorithmic bytes: six int32 per record read, the int32 map read and written once
+        nbytes = 24.0 * n_rec + 8.0 * s_la.n_inst * s_la.map_len
+        gbs = nbytes / call_s / 1e9
+        out["lookahead"] = {"bound": "hbm", "records": n_rec, "ms_per_call": 1e3 * call_s, "achieved": gbs,
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                            "records_per_s": n_rec / call_s}
+        del cols, kv, lws
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = time_cpu_oracle(model_path, batch, ant)

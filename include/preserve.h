@@ -53,7 +53,7 @@ typedef struct ps_status {
 #define PS_ST_BAD_TOKEN    0x01  /* token id outside [0, vocab)                               */
 #define PS_ST_BAD_LENGTH   0x02  /* request length < 1, > its span, or + n_soft > max_pos     */
 #define PS_ST_NAN          0x04  /* a prediction is NaN                                       */
-#define PS_ST_BAD_RECORD   0x10  /* anticipator record skipped: pred_tokens < 0 or > PS_MAX_PRED,
+#define PS_ST_BAD_RECORD   0x10  /* anticipator or look-ahead record skipped: pred_tokens < 0 or > PS_MAX_PRED,
                                     instance outside [0, n_inst), arrival outside [0, horizon),
                                     or rate[instance] < 1                                     */
 #define PS_ST_RANGE        0x20  /* a load bucket left the int32 range (its low 32 bits are stored),
@@ -139,6 +139,40 @@ int ps_anticipate(const int32_t* pred_tokens, const int32_t* instance_id,
                   int64_t n_req, int32_t n_inst, int32_t horizon,
                   int32_t* load, int64_t* overflow,
                   void* workspace, size_t workspace_bytes, ps_status* status, void* hip_stream);
+
+/* The load-look-ahead map in the paper's own units (Sec. 3.4.1): kv_tokens[k][t] is the number of
+ * KV-cache tokens instance k is expected to hold at the t-th decoding iteration from now (the paper
+ * records U = tokens / M, the fraction of the instance's token capacity M; see `fraction` below).
+ * Record j adds sign[j] * (prompt_tokens[j] + i) to slot start_iter[j] + i of instance
+ * instance_id[j] for every i in [i_begin[j], i_end[j]):
+ *   - a new request with P prompt tokens and D predicted response tokens whose first decoding
+ *     iteration is slot s:                      (k, s, P, 0, D, +1)    U'_i = (U_i M + (P + i)) / M
+ *   - one that finished after D' < D iterations: (k, s, P, D', D, -1)   the rest is subtracted
+ *   - one still running after D iterations:      (k, s, P, D, D + ext, +1)  a virtual extension, whose
+ *     unused part is subtracted like an early finish once the request completes.
+ *   instance_id, start_iter, prompt_tokens, i_begin, i_end, sign   [n_rec] int32 each
+ *   n_rec, n_inst, map_len  host scalars; map_len <= PS_MAX_ITER + 1
+ *   kv_tokens  [n_inst * map_len] int32, row-major, ACCUMULATED into (zero it to build from scratch)
+ *   overflow   [n_inst] int64 or NULL, accumulated: signed tokens of iterations at or beyond map_len
+ *   capacity   [n_inst] int32 token capacities M, needed only with `fraction`
+ *   fraction   [n_inst * map_len] float or NULL, out: kv_tokens / capacity after the update (NaN for
+ *              an instance whose capacity is < 1)
+ *   workspace  device scratch of at least ps_lookahead_workspace_bytes(n_inst, map_len) bytes,
+ *              256-byte aligned; contents undefined before and after
+ *   status     device ps_status or NULL.  A record with instance outside [0, n_inst), start_iter
+ *              outside [0, map_len), prompt_tokens outside [0, 2^20), i_begin < 0, i_end < i_begin,
+ *              i_end > PS_MAX_ITER or sign not +1 / -1 is skipped (PS_ST_BAD_RECORD); a slot that
+ *              leaves the int32 range keeps its low 32 bits (PS_ST_RANGE).
+ * Integer arithmetic throughout: the result does not depend on record order and is bit-exact.
+ * n_rec == 0 is allowed (with `fraction` it recomputes the fractions of the map as it stands).
+ * Errors: PS_EINVAL, PS_EWORKSPACE, PS_EUNSUPPORTED (map_len above PS_MAX_ITER + 1), PS_EHIP. */
+#define PS_MAX_ITER  65535       /* largest i_end ps_lookahead_update accepts                 */
+size_t ps_lookahead_workspace_bytes(int32_t n_inst, int32_t map_len);
+int ps_lookahead_update(const int32_t* instance_id, const int32_t* start_iter,
+                        const int32_t* prompt_tokens, const int32_t* i_begin, const int32_t* i_end,
+                        const int32_t* sign, int64_t n_rec, int32_t n_inst, int32_t map_len,
+                        int32_t* kv_tokens, int64_t* overflow, const int32_t* capacity, float* fraction,
+                        void* workspace, size_t workspace_bytes, ps_status* status, void* hip_stream);
 
 /* Kernel-family timing for benchmarks.  While enabled, ps_predict_load() brackets every kernel
  * launch with HIP events on the call's stream (the paper reports only the predictor's end-to-end

@@ -21,7 +21,8 @@ PS_ST_BAD_TOKEN, PS_ST_BAD_LENGTH, PS_ST_NAN, PS_ST_BAD_RECORD, PS_ST_RANGE = 0x
 
 EXPORTS = ["ps_model_load", "ps_model_free", "ps_model_get_info", "ps_workspace_bytes", "ps_predict_load",
            "ps_anticipate_workspace_bytes", "ps_anticipate", "ps_status_read", "ps_strerror",
-           "ps_profile_enable", "ps_profile_read", "ps_profile_clock"]
+           "ps_profile_enable", "ps_profile_read", "ps_profile_clock",
+           "ps_lookahead_workspace_bytes", "ps_lookahead_update"]
 PS_FAMILIES = ["embed", "gemm", "attention", "layernorm", "head", "refine"]
 
 
@@ -66,6 +67,10 @@ def load_library() -> ctypes.CDLL:
     lib.ps_anticipate_workspace_bytes.argtypes = [i64, i32, i32]
     lib.ps_anticipate.restype = ctypes.c_int
     lib.ps_anticipate.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp, vp]
+    lib.ps_lookahead_workspace_bytes.restype = sz
+    lib.ps_lookahead_workspace_bytes.argtypes = [i32, i32]
+    lib.ps_lookahead_update.restype = ctypes.c_int
+    lib.ps_lookahead_update.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp, vp]
     lib.ps_status_read.restype = ctypes.c_int
     lib.ps_status_read.argtypes = [vp, vp, ctypes.POINTER(ps_status)]
     lib.ps_profile_enable.restype = ctypes.c_int
@@ -192,6 +197,31 @@ def ps_anticipate(pred_tokens: torch.Tensor, instance_id: torch.Tensor, arrival_
         pred_tokens.numel(), n_inst, horizon, _ptr(load, torch.int32, "load"),
         _ptr(overflow, torch.int64, "overflow"), _ptr(workspace, torch.uint8, "workspace"),
         workspace.numel(), _ptr(status, torch.int64, "status"), _stream()), "ps_anticipate")
+
+
+def ps_lookahead_workspace_bytes(n_inst: int, map_len: int) -> int:
+    return int(load_library().ps_lookahead_workspace_bytes(n_inst, map_len))
+
+
+def ps_lookahead_update(instance_id: torch.Tensor, start_iter: torch.Tensor, prompt_tokens: torch.Tensor,
+                        i_begin: torch.Tensor, i_end: torch.Tensor, sign: torch.Tensor, n_inst: int, map_len: int,
+                        kv_tokens: torch.Tensor, overflow: Optional[torch.Tensor], workspace: torch.Tensor,
+                        capacity: Optional[torch.Tensor] = None, fraction: Optional[torch.Tensor] = None,
+                        status: Optional[torch.Tensor] = None) -> None:
+    cols = (instance_id, start_iter, prompt_tokens, i_begin, i_end, sign)
+    n = instance_id.numel()
+    if any(c.numel() != n for c in cols) or kv_tokens.numel() != n_inst * map_len or \
+            (overflow is not None and overflow.numel() != n_inst) or \
+            (capacity is not None and capacity.numel() != n_inst) or \
+            (fraction is not None and fraction.numel() != n_inst * map_len):
+        raise ValueError("ps_lookahead_update: array sizes do not match n_rec / n_inst / map_len")
+    names = ("instance_id", "start_iter", "prompt_tokens", "i_begin", "i_end", "sign")
+    _check(load_library().ps_lookahead_update(
+        *[_ptr(c, torch.int32, nm) for c, nm in zip(cols, names)], n, n_inst, map_len,
+        _ptr(kv_tokens, torch.int32, "kv_tokens"), _ptr(overflow, torch.int64, "overflow"),
+        _ptr(capacity, torch.int32, "capacity"), _ptr(fraction, torch.float32, "fraction"),
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _ptr(status, torch.int64, "status"),
+        _stream()), "ps_lookahead_update")
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:

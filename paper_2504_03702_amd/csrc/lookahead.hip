@@ -1,0 +1,146 @@
+// Load-look-ahead map in the paper's own units (Sec. 3.4.1): per instance, the KV-cache tokens
+// expected to be resident at each of the next map_len decoding iterations.
+//
+// A record (instance k, slot s, prompt P, i_begin, i_end, sign) adds sign * (P + i) to slot s + i
+// for i in [i_begin, i_end): the admission of a request (i in [0, D), +1), the removal of the rest
+// of one that finished early (i in [D', D), -1) or a virtual extension of one that runs long.  The
+// ramp is linear, so it is four point updates of the row's SECOND difference h:
+//     h[lo] += v0, h[lo + 1] += sign - v0, h[hi] -= v1 + sign, h[hi + 1] += v1,
+// lo = s + i_begin, hi = s + i_end, v0 = sign (P + i_begin), v1 = sign (P + i_end - 1)
+// (they overlap correctly for a ramp of one slot), and the map is the double prefix sum
+//     N[t] = sum_{v <= t} (t - v + 1) h[v] = (t + 1) S0[t] - S1[t],  S0 = prefix(h), S1 = prefix(v h[v]).
+// Updates at or beyond map_len never reach a slot inside the map and are dropped; the tokens of
+// iterations beyond the map go to overflow[] in closed form.  A record costs four 64-bit integer
+// atomic adds whatever its length; rows here are long (thousands of iterations), so the differences
+// live in an L2-resident global array rather than in LDS.  Kernels: clear the differences; one
+// thread per record applies its updates; one workgroup per instance scans its row, accumulates into
+// the caller's map and, if asked, writes the fraction of the instance's token capacity.  Integer
+// arithmetic throughout: the result is exact and independent of record order.
+#include "device_util.h"
+#include "internal.h"
+
+namespace {
+
+__global__ __launch_bounds__(256) void lookahead_clear_kernel(ulonglong2* __restrict__ d2, int64_t n16) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256)
+        d2[i] = make_ulonglong2(0ull, 0ull);
+}
+
+__global__ __launch_bounds__(256) void lookahead_scatter_kernel(
+    const int32_t* __restrict__ instance_id, const int32_t* __restrict__ start_iter,
+    const int32_t* __restrict__ prompt_tokens, const int32_t* __restrict__ i_begin,
+    const int32_t* __restrict__ i_end, const int32_t* __restrict__ sign, int64_t n, int n_inst, int map_len,
+    unsigned long long* __restrict__ d2, int64_t* __restrict__ overflow, ps_status* st) {
+    for (int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x; r < n; r += (int64_t)gridDim.x * 256) {
+        const int k = instance_id[r], s = start_iter[r], P = prompt_tokens[r];
+        const int b = i_begin[r], e = i_end[r], sg = sign[r];
+        if ((unsigned)k >= (unsigned)n_inst || (unsigned)s >= (unsigned)map_len || (unsigned)P >= (1u << 20) || b < 0 ||
+            e < b || e > PS_MAX_ITER || (sg != 1 && sg != -1)) {
+            report_fault(st, PS_ST_BAD_RECORD, r);
+            continue;
+        }
+        if (b == e) continue;
+        const long long v0 = (long long)sg * (P + b), v1 = (long long)sg * (P + e - 1);
+        const int64_t lo = (int64_t)s + b, hi = (int64_t)s + e;
+        unsigned long long* row = d2 + (int64_t)k * map_len;
+        if (lo < map_len) atomicAdd(row + lo, (unsigned long long)v0);
+        if (lo + 1 < map_len) atomicAdd(row + lo + 1, (unsigned long long)((long long)sg - v0));
+        if (hi < map_len) atomicAdd(row + hi, (unsigned long long)(-(v1 + sg)));
+        if (hi + 1 < map_len) atomicAdd(row + hi + 1, (unsigned long long)v1);
+        if (hi > map_len && overflow) {
+            // iterations io .. e - 1 fall beyond the map: c of them, sum of (P + i) in closed form
+            const long long io = max((long long)b, (long long)map_len - s), c = e - io;
+            const long long sum = c * P + (io + e - 1) * c / 2;
+            atomicAdd((unsigned long long*)(overflow + k), (unsigned long long)((long long)sg * sum));
+        }
+    }
+}
+
+// One workgroup per instance.  Slots are taken 1024 at a time, thread t owning the four consecutive
+// slots 4 t .. 4 t + 3; the two running sums S0 and S1 are scanned across the workgroup with
+// wavefront shuffles (64-bit), carried from chunk to chunk.
+__global__ __launch_bounds__(256) void lookahead_scan_kernel(const long long* __restrict__ d2, int n_inst, int map_len,
+                                                             int32_t* __restrict__ kv_tokens,
+                                                             const int32_t* __restrict__ capacity,
+                                                             float* __restrict__ fraction, ps_status* st) {
+    __shared__ long long s_w0[4], s_w1[4];
+    const int k = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long* h = d2 + (int64_t)k * map_len;
+    int32_t* out = kv_tokens + (int64_t)k * map_len;
+    float* frow = fraction ? fraction + (int64_t)k * map_len : nullptr;
+    const int cap = fraction ? capacity[k] : 1;
+    const float cap_f = cap >= 1 ? (float)cap : __builtin_nanf("");      // no capacity: fractions are NaN
+    long long carry0 = 0, carry1 = 0;
+    for (int t0 = 0; t0 < map_len; t0 += 1024) {
+        const int t = t0 + 4 * tid;
+        long long a0[4], a1[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const long long v = t + c < map_len ? h[t + c] : 0;
+            a0[c] = v;
+            a1[c] = v * (t + c);
+        }
+#pragma unroll
+        for (int c = 1; c < 4; ++c) { a0[c] += a0[c - 1]; a1[c] += a1[c - 1]; }
+        long long i0 = a0[3], i1 = a1[3];                       // inclusive scans of the thread totals
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const long long u0 = __shfl_up(i0, o, 64), u1 = __shfl_up(i1, o, 64);
+            if (lane >= o) { i0 += u0; i1 += u1; }
+        }
+        if (lane == 63) { s_w0[wave] = i0; s_w1[wave] = i1; }
+        __syncthreads();
+        long long before0 = carry0 + i0 - a0[3], before1 = carry1 + i1 - a1[3];
+        for (int w = 0; w < wave; ++w) { before0 += s_w0[w]; before1 += s_w1[w]; }
+        const long long tot0 = s_w0[0] + s_w0[1] + s_w0[2] + s_w0[3], tot1 = s_w1[0] + s_w1[1] + s_w1[2] + s_w1[3];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (t + c < map_len) {
+                const long long s0 = before0 + a0[c], s1 = before1 + a1[c];
+                const long long nv = (long long)out[t + c] + (long long)(t + c + 1) * s0 - s1;
+                if (nv > 2147483647ll || nv < -2147483648ll) report_fault(st, PS_ST_RANGE, -1);
+                out[t + c] = (int32_t)(uint32_t)(unsigned long long)nv;
+                if (frow) frow[t + c] = (float)nv / cap_f;
+            }
+        }
+        carry0 += tot0;
+        carry1 += tot1;
+        __syncthreads();
+    }
+}
+
+}  // namespace
+
+extern "C" size_t ps_lookahead_workspace_bytes(int32_t n_inst, int32_t map_len) {
+    if (n_inst < 1 || map_len < 1 || map_len > PS_MAX_ITER + 1) return 0;
+    return align_up((size_t)n_inst * (size_t)map_len * 8, 256);
+}
+
+extern "C" int ps_lookahead_update(const int32_t* instance_id, const int32_t* start_iter,
+                                   const int32_t* prompt_tokens, const int32_t* i_begin, const int32_t* i_end,
+                                   const int32_t* sign, int64_t n_rec, int32_t n_inst, int32_t map_len,
+                                   int32_t* kv_tokens, int64_t* overflow, const int32_t* capacity, float* fraction,
+                                   void* workspace, size_t workspace_bytes, ps_status* status, void* hip_stream) {
+    if (n_rec < 0 || n_inst < 1 || map_len < 1 || !kv_tokens) return PS_EINVAL;
+    if (fraction && !capacity) return PS_EINVAL;
+    if (map_len > PS_MAX_ITER + 1) return PS_EUNSUPPORTED;
+    if (n_rec > 0 && (!instance_id || !start_iter || !prompt_tokens || !i_begin || !i_end || !sign)) return PS_EINVAL;
+    if (n_rec == 0 && !fraction) return PS_OK;
+    const size_t need = ps_lookahead_workspace_bytes(n_inst, map_len);
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need) return PS_EWORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    (void)hipGetLastError();
+    const int64_t n16 = (int64_t)(need / 16);
+    const unsigned clear_blocks = (unsigned)((n16 + 255) / 256 < 2048 ? (n16 + 255) / 256 : 2048);
+    hipLaunchKernelGGL(lookahead_clear_kernel, dim3(clear_blocks), dim3(256), 0, s, (ulonglong2*)workspace, n16);
+    if (n_rec > 0) {
+        const int64_t want = (n_rec + 255) / 256;
+        const unsigned blocks = (unsigned)(want < 8192 ? want : 8192);
+        hipLaunchKernelGGL(lookahead_scatter_kernel, dim3(blocks), dim3(256), 0, s, instance_id, start_iter,
+                           prompt_tokens, i_begin, i_end, sign, n_rec, n_inst, map_len,
+                           (unsigned long long*)workspace, overflow, status);
+    }
+    hipLaunchKernelGGL(lookahead_scan_kernel, dim3((unsigned)n_inst), dim3(256), 0, s, (const long long*)workspace,
+                       n_inst, map_len, kv_tokens, capacity, fraction, status);
+    return hipGetLastError() == hipSuccess ? PS_OK : PS_EHIP;
+}

@@ -294,3 +294,69 @@ def make_anticipator_inputs(kind: str, seed: int = 0, n: Optional[int] = None,
         pred_tokens = np.asarray(pred_tokens, np.int32)
         assert pred_tokens.shape[0] == n
     return AnticipatorInputs(pred_tokens, instance, arrival, rate, n_inst, horizon)
+
+
+@dataclasses.dataclass
+class LookaheadInputs:
+    """Records of the look-ahead map in KV-token units (paper Sec. 3.4.1): one row per column."""
+    instance_id: np.ndarray
+    start_iter: np.ndarray
+    prompt_tokens: np.ndarray
+    i_begin: np.ndarray
+    i_end: np.ndarray
+    sign: np.ndarray
+    capacity: np.ndarray          # [n_inst] token capacity M of each instance
+    n_inst: int
+    map_len: int
+
+    def columns(self):
+        return (self.instance_id, self.start_iter, self.prompt_tokens, self.i_begin, self.i_end, self.sign)
+
+
+def make_lookahead_inputs(kind: str, seed: int = 0, n: Optional[int] = None,
+                          pred_tokens: Optional[np.ndarray] = None,
+                          prompt_tokens: Optional[np.ndarray] = None) -> LookaheadInputs:
+    """A stream of map updates: every request is admitted (ramp over [0, D)); a share of them also
+    carries its correction, as the paper describes them: finished early after D' < D iterations (the
+    rest subtracted), or still running at D (a virtual extension of ceil(0.2 D) iterations added, its
+    unused part subtracted when the request completes inside it).  Prompt lengths follow the prompt
+    statistics (lognormal, median 52, clipped to [7, 2048]) unless given, response lengths the
+    response statistics unless given; the map has one slot per decoding iteration up to the model's
+    maximum output (4096); start slots are uniform over the first quarter of the map."""
+    rng = np.random.default_rng(seed + 5000)
+    if kind == "tiny":
+        n_inst, map_len, n = 3, 64, n or 24
+    elif kind == "medium":
+        n_inst, map_len, n = 64, 1024, n or 2048
+    elif kind in ("production", "stream"):
+        n_inst, map_len = 256, 4096
+        n = n or (4096 if kind == "production" else 10_000_000)
+    else:
+        raise ValueError(kind)
+    if pred_tokens is None:
+        d = np.clip(np.rint(np.exp(rng.normal(np.log(87.0), 1.3, n))), 1, 4096).astype(np.int64)
+    else:
+        d = np.clip(np.asarray(pred_tokens, np.int64), 0, 4096)
+    if prompt_tokens is None:
+        p = np.clip(np.rint(np.exp(rng.normal(np.log(52.0), 1.2, n))), 7, 2048).astype(np.int64)
+    else:
+        p = np.asarray(prompt_tokens, np.int64)
+    if kind == "tiny":
+        d, p = np.minimum(d, 40), np.minimum(p, 30)
+    k = rng.integers(0, n_inst, n)
+    s = rng.integers(0, max(map_len // 4, 1), n)
+    fate = rng.random(n)
+    early = fate < 0.3
+    late = (fate >= 0.3) & (fate < 0.5)
+    d_hat = np.where(early, (rng.random(n) * d).astype(np.int64), d)           # D' in [0, D)
+    ext = np.ceil(0.2 * d).astype(np.int64)
+    used = np.where(late, np.minimum(ext, (rng.random(n) * (ext + 1)).astype(np.int64)), 0)
+    cols = [np.stack([k, s, p, np.zeros(n, np.int64), d, np.ones(n, np.int64)], 1),
+            np.stack([k, s, p, d_hat, d, -np.ones(n, np.int64)], 1)[early],
+            np.stack([k, s, p, d, d + ext, np.ones(n, np.int64)], 1)[late],
+            np.stack([k, s, p, d + used, d + ext, -np.ones(n, np.int64)], 1)[late]]
+    rec = np.concatenate(cols, 0)
+    rec = rec[rng.permutation(rec.shape[0])].astype(np.int32)
+    capacity = rng.integers(120_000, 400_001, n_inst).astype(np.int32)
+    return LookaheadInputs(*[np.ascontiguousarray(rec[:, c]) for c in range(6)], capacity, n_inst, map_len)
+

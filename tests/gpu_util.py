@@ -45,3 +45,25 @@ def run_anticipate(inp, load=None, overflow=None, dev="cuda:0"):
                      inp.horizon, load_t, ovf_t, ws, st)
     flags, bad = ps.ps_status_read(st)
     return load_t.cpu().numpy().reshape(inp.n_inst, inp.horizon), ovf_t.cpu().numpy(), flags, bad
+
+
+def run_lookahead(cols, n_inst, map_len, kv=None, overflow=None, capacity=None, want_fraction=False,
+                  with_overflow=True, dev="cuda:0"):
+    """ps_lookahead_update on numpy columns (instance, start, prompt, i_begin, i_end, sign).
+    Returns (kv_tokens, overflow, fraction or None, flags, first_bad)."""
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.int32)).to(dev)
+    kv_t = torch.zeros(n_inst * map_len, dtype=torch.int32, device=dev) if kv is None \
+        else torch.from_numpy(np.ascontiguousarray(kv, np.int32).reshape(-1)).to(dev)
+    ovf_t = None
+    if with_overflow:
+        ovf_t = torch.zeros(n_inst, dtype=torch.int64, device=dev) if overflow is None \
+            else torch.from_numpy(np.ascontiguousarray(overflow, np.int64)).to(dev)
+    cap_t = None if capacity is None else t(capacity)
+    frac_t = torch.full((n_inst * map_len,), -1.0, dtype=torch.float32, device=dev) if want_fraction else None
+    ws = ps.alloc_workspace(ps.ps_lookahead_workspace_bytes(n_inst, map_len), dev)
+    ws.fill_(0xA5)                               # the library must not rely on a clean workspace
+    st = ps.new_status(dev)
+    ps.ps_lookahead_update(*[t(c) for c in cols], n_inst, map_len, kv_t, ovf_t, ws, cap_t, frac_t, st)
+    flags, bad = ps.ps_status_read(st)
+    return (kv_t.cpu().numpy().reshape(n_inst, map_len), None if ovf_t is None else ovf_t.cpu().numpy(),
+            None if frac_t is None else frac_t.cpu().numpy().reshape(n_inst, map_len), flags, bad)

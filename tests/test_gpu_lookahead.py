@@ -1,0 +1,118 @@
+"""GPU parity of ps_lookahead_update (the look-ahead map in KV-token units, paper Sec. 3.4.1)
+against the C oracle on the same seeded records, through the C ABI: bit-exact integers."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lookahead as ol
+from paper_2504_03702_amd import binding as ps
+from paper_2504_03702_amd import workloads as wl
+from tests.gpu_util import run_lookahead
+from tests.test_oracle_lookahead import read_cases
+
+pytestmark = pytest.mark.gpu
+
+
+def both(cols, n_inst, map_len, **kw):
+    got = run_lookahead(cols, n_inst, map_len, **kw)
+    ref = ol.lookahead_update(*cols, n_inst, map_len, kv_tokens=kw.get("kv"), overflow=kw.get("overflow"))
+    return got, ref
+
+
+@pytest.mark.parametrize("case", read_cases(), ids=lambda c: c["name"])
+def test_hand_cases(case):
+    print(f"lookahead hand case {case['name']}", flush=True)
+    a = np.array(case["recs"], np.int32).reshape(-1, 6)
+    (kv, ovf, _, flags, _), (rkv, rovf, rst, _) = both([a[:, c] for c in range(6)], case["n_inst"], case["map_len"])
+    assert flags == 0 and rst == 0
+    assert np.array_equal(kv, rkv) and np.array_equal(ovf, rovf)
+
+
+@pytest.mark.parametrize("kind,n", [("tiny", None), ("medium", None), ("production", None), ("production", 300_000)])
+def test_streams_bit_exact_with_fractions(kind, n):
+    print(f"lookahead stream {kind} n={n}", flush=True)
+    x = wl.make_lookahead_inputs(kind, seed=1, n=n)
+    (kv, ovf, frac, flags, _), (rkv, rovf, rst, _) = both(x.columns(), x.n_inst, x.map_len, capacity=x.capacity,
+                                                           want_fraction=True)
+    assert flags == 0 and rst == 0
+    assert np.array_equal(kv, rkv) and np.array_equal(ovf, rovf)
+    assert kv.min() >= 0                                   # corrections never take out more than was put in
+    want = ol.fraction(rkv, x.capacity)
+    np.testing.assert_allclose(frac, want, rtol=2.0 ** -23, atol=0)
+
+
+def test_accumulates_and_is_order_free():
+    x = wl.make_lookahead_inputs("medium", seed=2)
+    cols = [c.copy() for c in x.columns()]
+    half = len(cols[0]) // 2
+    kv1, ovf1, _, f1, _ = run_lookahead([c[:half] for c in cols], x.n_inst, x.map_len)
+    kv2, ovf2, _, f2, _ = run_lookahead([c[half:] for c in cols], x.n_inst, x.map_len, kv=kv1, overflow=ovf1)
+    perm = np.random.default_rng(0).permutation(len(cols[0]))
+    kv3, ovf3, _, f3, _ = run_lookahead([c[perm] for c in cols], x.n_inst, x.map_len)
+    rkv, rovf, _, _ = ol.lookahead_update(*cols, x.n_inst, x.map_len)
+    assert f1 == f2 == f3 == 0
+    assert np.array_equal(kv2, rkv) and np.array_equal(kv3, rkv)
+    assert np.array_equal(ovf2, rovf) and np.array_equal(ovf3, rovf)
+
+
+@pytest.mark.parametrize("map_len", [1, 2, 3, 1023, 1024, 1025, 65536])
+def test_map_lengths_and_ramps_crossing_the_end(map_len):
+    print(f"lookahead map_len={map_len}", flush=True)
+    rng = np.random.default_rng(map_len)
+    n, K = 400, 3
+    cols = [rng.integers(0, K, n), rng.integers(0, map_len, n), rng.integers(0, 5000, n),
+            rng.integers(0, 40, n), None, rng.choice([-1, 1], n)]
+    cols[4] = cols[3] + rng.integers(0, min(2 * map_len, 65535 - 40) + 1, n)
+    cols = [np.asarray(c, np.int32) for c in cols]
+    (kv, ovf, _, flags, _), (rkv, rovf, rst, _) = both(cols, K, map_len)
+    assert flags == 0 and rst == 0
+    assert np.array_equal(kv, rkv) and np.array_equal(ovf, rovf)
+
+
+def test_bad_records_are_skipped_and_the_first_is_named():
+    x = wl.make_lookahead_inputs("medium", seed=3)
+    cols = [c.copy() for c in x.columns()]
+    bad_at = {700: (0, x.n_inst), 33: (1, -1), 1500: (2, 1 << 20), 90: (3, -1), 91: (4, 65536), 2000: (5, 0)}
+    for r, (c, v) in bad_at.items():
+        cols[c][r] = v
+    cols[3][91] = 0
+    (kv, ovf, _, flags, first), (rkv, rovf, rst, rfirst) = both(cols, x.n_inst, x.map_len)
+    assert rst == 1 and rfirst == 33
+    assert flags == ps.PS_ST_BAD_RECORD and first == 33
+    assert np.array_equal(kv, rkv) and np.array_equal(ovf, rovf)
+
+
+def test_int32_range_is_flagged_low_bits_kept():
+    cols = [np.array([0], np.int32), np.array([0], np.int32), np.array([1000], np.int32), np.array([0], np.int32),
+            np.array([2], np.int32), np.array([1], np.int32)]
+    base = np.full((1, 4), 2**31 - 1001, np.int32)
+    (kv, _, _, flags, _), (rkv, _, rst, _) = both(cols, 1, 4, kv=base)
+    assert rst == 2 and flags == ps.PS_ST_RANGE
+    assert np.array_equal(kv, rkv)
+
+
+def test_no_records_no_overflow_array_and_fraction_only():
+    dev = "cuda:0"
+    x = wl.make_lookahead_inputs("tiny", seed=4)
+    kv, _, _, flags, _ = run_lookahead(x.columns(), x.n_inst, x.map_len, with_overflow=False)
+    rkv, _, _, _ = ol.lookahead_update(*x.columns(), x.n_inst, x.map_len)
+    assert flags == 0 and np.array_equal(kv, rkv)
+    # no records: the map is left alone and its fractions are recomputed; capacity < 1 gives NaN
+    cap = x.capacity.copy()
+    cap[1] = 0
+    empty = [np.zeros(0, np.int32)] * 6
+    kv2, _, frac, flags, _ = run_lookahead(empty, x.n_inst, x.map_len, kv=kv, capacity=cap, want_fraction=True)
+    assert flags == 0 and np.array_equal(kv2, kv)
+    assert np.isnan(frac[1]).all()
+    np.testing.assert_allclose(frac[[0, 2]], ol.fraction(kv[[0, 2]], cap[[0, 2]]), rtol=2.0 ** -23)
+    # argument checks
+    z = torch.zeros(4, dtype=torch.int32, device=dev)
+    ws = ps.alloc_workspace(ps.ps_lookahead_workspace_bytes(1, 4), dev)
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_lookahead_update(z[:1], z[:1], z[:1], z[:1], z[:1], z[:1], 1, 4, z, None, ws[:16])
+    assert e.value.code == -5            # PS_EWORKSPACE
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_lookahead_update(z[:1], z[:1], z[:1], z[:1], z[:1], z[:1], 1, 4, z, None, ws,
+                               fraction=torch.zeros(4, device=dev))
+    assert e.value.code == -1            # PS_EINVAL
+    assert ps.ps_lookahead_workspace_bytes(1, 65537) == 0 and ps.ps_lookahead_workspace_bytes(0, 8) == 0
