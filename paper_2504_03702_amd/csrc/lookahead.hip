@@ -3,18 +3,19 @@
 //
 // A record (instance k, slot s, prompt P, i_begin, i_end, sign) adds sign * (P + i) to slot s + i
 // for i in [i_begin, i_end): the admission of a request (i in [0, D), +1), the removal of the rest
-// of one that finished early (i in [D', D), -1) or a virtual extension of one that runs long.  The
-// ramp is linear, so it is four point updates of the row's SECOND difference h:
-//     h[lo] += v0, h[lo + 1] += sign - v0, h[hi] -= v1 + sign, h[hi + 1] += v1,
-// lo = s + i_begin, hi = s + i_end, v0 = sign (P + i_begin), v1 = sign (P + i_end - 1)
-// (they overlap correctly for a ramp of one slot), and the map is the double prefix sum
-//     N[t] = sum_{v <= t} (t - v + 1) h[v] = (t + 1) S0[t] - S1[t],  S0 = prefix(h), S1 = prefix(v h[v]).
-// Updates at or beyond map_len never reach a slot inside the map and are dropped; the tokens of
-// iterations beyond the map go to overflow[] in closed form.  A record costs four 64-bit integer
-// atomic adds whatever its length; rows here are long (thousands of iterations), so the differences
-// live in an L2-resident global array rather than in LDS.  Kernels: clear the differences; one
-// thread per record applies its updates; one workgroup per instance scans its row, accumulates into
-// the caller's map and, if asked, writes the fraction of the instance's token capacity.  Integer
+// of one that finished early (i in [D', D), -1) or a virtual extension of one that runs long.  In
+// terms of the slot t = s + i the amount is sign (P - s) + sign t, an offset and a slope that are
+// constant over the record's slots [lo, hi) = [s + i_begin, s + i_end).  So with two difference
+// arrays, dA[lo] += sign (P - s), dA[hi] -= sign (P - s) and dB[lo] += sign, dB[hi] -= sign,
+// the map is N[t] = prefix(dA)[t] + t * prefix(dB)[t].  Both differences of a slot travel in one
+// 64-bit word, offset * 2^24 + slope (sums of signed numbers add component-wise as long as the slope
+// part stays below 2^23 in magnitude, i.e. fewer than 8 million records start or end in one slot), so a
+// record costs two 64-bit integer atomic adds whatever its length.  Updates at or beyond map_len
+// never reach a slot inside the map and are dropped; the tokens of iterations beyond the map go to
+// overflow[] in closed form.  Rows here are long (thousands of iterations), so the differences live in
+// an L2-resident global array rather than in LDS.  Kernels: clear the differences; one thread per
+// record applies its updates; one workgroup per instance scans its row, accumulates into the
+// caller's map and, if asked, writes the fraction of the instance's token capacity.  Integer
 // arithmetic throughout: the result is exact and independent of record order.
 #include "device_util.h"
 #include "internal.h"
@@ -40,13 +41,11 @@ __global__ __launch_bounds__(256) void lookahead_scatter_kernel(
             continue;
         }
         if (b == e) continue;
-        const long long v0 = (long long)sg * (P + b), v1 = (long long)sg * (P + e - 1);
         const int64_t lo = (int64_t)s + b, hi = (int64_t)s + e;
+        const long long word = (long long)sg * (P - s) * (1ll << 24) + sg;     // offset and slope, packed
         unsigned long long* row = d2 + (int64_t)k * map_len;
-        if (lo < map_len) atomicAdd(row + lo, (unsigned long long)v0);
-        if (lo + 1 < map_len) atomicAdd(row + lo + 1, (unsigned long long)((long long)sg - v0));
-        if (hi < map_len) atomicAdd(row + hi, (unsigned long long)(-(v1 + sg)));
-        if (hi + 1 < map_len) atomicAdd(row + hi + 1, (unsigned long long)v1);
+        if (lo < map_len) atomicAdd(row + lo, (unsigned long long)word);
+        if (hi < map_len) atomicAdd(row + hi, (unsigned long long)(-word));
         if (hi > map_len && overflow) {
             // iterations io .. e - 1 fall beyond the map: c of them, sum of (P + i) in closed form
             const long long io = max((long long)b, (long long)map_len - s), c = e - io;
@@ -57,7 +56,7 @@ __global__ __launch_bounds__(256) void lookahead_scatter_kernel(
 }
 
 // One workgroup per instance.  Slots are taken 1024 at a time, thread t owning the four consecutive
-// slots 4 t .. 4 t + 3; the two running sums S0 and S1 are scanned across the workgroup with
+// slots 4 t .. 4 t + 3; the two running sums (offsets, slopes) are scanned across the workgroup with
 // wavefront shuffles (64-bit), carried from chunk to chunk.
 __global__ __launch_bounds__(256) void lookahead_scan_kernel(const long long* __restrict__ d2, int n_inst, int map_len,
                                                              int32_t* __restrict__ kv_tokens,
@@ -73,12 +72,13 @@ __global__ __launch_bounds__(256) void lookahead_scan_kernel(const long long* __
     long long carry0 = 0, carry1 = 0;
     for (int t0 = 0; t0 < map_len; t0 += 1024) {
         const int t = t0 + 4 * tid;
-        long long a0[4], a1[4];
+        long long a0[4], a1[4];                                 // offset differences, slope differences
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const long long v = t + c < map_len ? h[t + c] : 0;
-            a0[c] = v;
-            a1[c] = v * (t + c);
+            const long long slope = (long long)((unsigned long long)v << 40) >> 40;      // low 24 bits, signed
+            a1[c] = slope;
+            a0[c] = (v - slope) >> 24;                          // exact: the remainder is a multiple of 2^24
         }
 #pragma unroll
         for (int c = 1; c < 4; ++c) { a0[c] += a0[c - 1]; a1[c] += a1[c - 1]; }
@@ -96,8 +96,7 @@ __global__ __launch_bounds__(256) void lookahead_scan_kernel(const long long* __
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             if (t + c < map_len) {
-                const long long s0 = before0 + a0[c], s1 = before1 + a1[c];
-                const long long nv = (long long)out[t + c] + (long long)(t + c + 1) * s0 - s1;
+                const long long nv = (long long)out[t + c] + (before0 + a0[c]) + (long long)(t + c) * (before1 + a1[c]);
                 if (nv > 2147483647ll || nv < -2147483648ll) report_fault(st, PS_ST_RANGE, -1);
                 out[t + c] = (int32_t)(uint32_t)(unsigned long long)nv;
                 if (frow) frow[t + c] = (float)nv / cap_f;
