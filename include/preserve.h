@@ -174,6 +174,25 @@ int ps_lookahead_update(const int32_t* instance_id, const int32_t* start_iter,
                         int32_t* kv_tokens, int64_t* overflow, const int32_t* capacity, float* fraction,
                         void* workspace, size_t workspace_bytes, ps_status* status, void* hip_stream);
 
+/* In-window checks of the proactive instance scaler (Sec. 3.4.2) on the look-ahead maps of
+ * ps_lookahead_update().  Over the next `window` iterations (clipped to map_len), U = tokens / capacity:
+ *   over_count[k]   iterations in which instance k's usage exceeds over_pct % (the paper: 95)
+ *   peak_tokens[k]  its largest token count in the window
+ *   overloaded[k]   1 if over_count[k] is more than share_pct % of the window (the paper: 10), else 0
+ *   summary[0]      number of overloaded instances (each asks for one more instance)
+ *   summary[1]      1 if every instance stays below idle_pct % (the paper's T_f = 30) throughout the
+ *                   window, i.e. a scale-down may be triggered, else 0
+ *   scale_down[0]   n_inst - sum_k(peak_tokens[k] / capacity[k]) / (idle_pct / 100): the number of
+ *                   instances to isolate if summary[1] is set (a double; the caller rounds)
+ * kv_tokens [n_inst * map_len] int32, capacity [n_inst] int32; over_count, peak_tokens, overloaded
+ * [n_inst] int32; summary [2] int32; scale_down [1] double; all device, all outputs overwritten.
+ * Thresholds are whole percents and compared in integers, so the flags are exact.  An instance with
+ * capacity < 1 is left out (zeros) and clears summary[1].  Errors: PS_EINVAL, PS_EHIP. */
+int ps_scaler_scan(const int32_t* kv_tokens, const int32_t* capacity, int32_t n_inst, int32_t map_len,
+                   int32_t window, int32_t over_pct, int32_t share_pct, int32_t idle_pct,
+                   int32_t* over_count, int32_t* peak_tokens, int32_t* overloaded, int32_t* summary,
+                   double* scale_down, void* hip_stream);
+
 /* Kernel-family timing for benchmarks.  While enabled, ps_predict_load() brackets every kernel
  * launch with HIP events on the call's stream (the paper reports only the predictor's end-to-end
  * latency, Sec. 4.5; this splits it by kernel).  ps_profile_read() waits for `hip_stream`, adds

@@ -22,7 +22,7 @@ PS_ST_BAD_TOKEN, PS_ST_BAD_LENGTH, PS_ST_NAN, PS_ST_BAD_RECORD, PS_ST_RANGE = 0x
 EXPORTS = ["ps_model_load", "ps_model_free", "ps_model_get_info", "ps_workspace_bytes", "ps_predict_load",
            "ps_anticipate_workspace_bytes", "ps_anticipate", "ps_status_read", "ps_strerror",
            "ps_profile_enable", "ps_profile_read", "ps_profile_clock",
-           "ps_lookahead_workspace_bytes", "ps_lookahead_update"]
+           "ps_lookahead_workspace_bytes", "ps_lookahead_update", "ps_scaler_scan"]
 PS_FAMILIES = ["embed", "gemm", "attention", "layernorm", "head", "refine"]
 
 
@@ -71,6 +71,8 @@ def load_library() -> ctypes.CDLL:
     lib.ps_lookahead_workspace_bytes.argtypes = [i32, i32]
     lib.ps_lookahead_update.restype = ctypes.c_int
     lib.ps_lookahead_update.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp, vp]
+    lib.ps_scaler_scan.restype = ctypes.c_int
+    lib.ps_scaler_scan.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.ps_status_read.restype = ctypes.c_int
     lib.ps_status_read.argtypes = [vp, vp, ctypes.POINTER(ps_status)]
     lib.ps_profile_enable.restype = ctypes.c_int
@@ -222,6 +224,21 @@ def ps_lookahead_update(instance_id: torch.Tensor, start_iter: torch.Tensor, pro
         _ptr(capacity, torch.int32, "capacity"), _ptr(fraction, torch.float32, "fraction"),
         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _ptr(status, torch.int64, "status"),
         _stream()), "ps_lookahead_update")
+
+
+def ps_scaler_scan(kv_tokens: torch.Tensor, capacity: torch.Tensor, n_inst: int, map_len: int, window: int,
+                   over_count: torch.Tensor, peak_tokens: torch.Tensor, overloaded: torch.Tensor,
+                   summary: torch.Tensor, scale_down: torch.Tensor, over_pct: int = 95, share_pct: int = 10,
+                   idle_pct: int = 30) -> None:
+    if kv_tokens.numel() != n_inst * map_len or capacity.numel() != n_inst or summary.numel() != 2 or \
+            scale_down.numel() != 1 or any(t.numel() != n_inst for t in (over_count, peak_tokens, overloaded)):
+        raise ValueError("ps_scaler_scan: array sizes do not match n_inst / map_len")
+    _check(load_library().ps_scaler_scan(
+        _ptr(kv_tokens, torch.int32, "kv_tokens"), _ptr(capacity, torch.int32, "capacity"), n_inst, map_len, window,
+        over_pct, share_pct, idle_pct, _ptr(over_count, torch.int32, "over_count"),
+        _ptr(peak_tokens, torch.int32, "peak_tokens"), _ptr(overloaded, torch.int32, "overloaded"),
+        _ptr(summary, torch.int32, "summary"), _ptr(scale_down, torch.float64, "scale_down"), _stream()),
+        "ps_scaler_scan")
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:

@@ -116,3 +116,48 @@ def test_no_records_no_overflow_array_and_fraction_only():
                                fraction=torch.zeros(4, device=dev))
     assert e.value.code == -1            # PS_EINVAL
     assert ps.ps_lookahead_workspace_bytes(1, 65537) == 0 and ps.ps_lookahead_workspace_bytes(0, 8) == 0
+
+
+def run_scaler(kv, cap, window, dev="cuda:0", **pct):
+    K, L = kv.shape
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.int32)).to(dev)
+    oc, pk, ov = (torch.full((K,), -9, dtype=torch.int32, device=dev) for _ in range(3))
+    summ = torch.full((2,), -9, dtype=torch.int32, device=dev)
+    sd = torch.full((1,), -9.0, dtype=torch.float64, device=dev)
+    ps.ps_scaler_scan(t(kv).reshape(-1), t(cap), K, L, window, oc, pk, ov, summ, sd, **pct)
+    s = summ.cpu().numpy()
+    return oc.cpu().numpy(), pk.cpu().numpy(), ov.cpu().numpy(), int(s[0]), int(s[1]), float(sd.cpu()[0])
+
+
+@pytest.mark.parametrize("window", [0, 1, 63, 64, 100, 4096, 100000])
+def test_scaler_checks_match_the_oracle(window):
+    from oracle import scaler as osc
+    print(f"scaler scan window={window}", flush=True)
+    x = wl.make_lookahead_inputs("production", seed=5, n=60_000)
+    kv, _, _, _ = ol.lookahead_update(*x.columns(), x.n_inst, x.map_len)
+    cap = (x.capacity // 40).astype(np.int32)              # small capacities: some instances run hot
+    cap[3] = 0
+    kv[7] = 0                                              # an idle instance
+    got = run_scaler(kv, cap, window)
+    ref = osc.scaler_scan(kv, cap, window)
+    for g, r in zip(got[:3], ref[:3]):
+        assert np.array_equal(g, r)
+    assert got[3] == ref[3] and got[4] == ref[4]
+    assert abs(got[5] - ref[5]) <= 1e-9 * max(1.0, abs(ref[5]))
+    if 100 <= window <= 4096:
+        assert 0 < ref[3] < x.n_inst                       # the case exercises both outcomes
+
+
+def test_scaler_boundaries_and_scale_down():
+    from oracle import scaler as osc
+    kv = np.zeros((4, 128), np.int32)
+    kv[0, :10], kv[1, :11], kv[2, :50] = 951, 951, 950
+    kv[2, 100:] = 999
+    got = run_scaler(kv, [1000] * 4, 100)
+    ref = osc.scaler_scan(kv, [1000] * 4, 100)
+    assert got[2].tolist() == [0, 1, 0, 0] == ref[2].tolist() and got[4] == 0
+    calm = np.zeros((4, 64), np.int32)
+    calm[0, 5], calm[1, 63], calm[2, 0], calm[3, 7] = 299, 100, 149, 10
+    got = run_scaler(calm, [1000, 2000, 500, 400], 64)
+    assert got[3] == 0 and got[4] == 1
+    assert abs(got[5] - (4 - (0.299 + 0.05 + 0.298 + 0.025) / 0.3)) < 1e-12
