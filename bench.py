@@ -286,6 +286,28 @@ def main() -> int:
                             "records_per_s": n_rec / call_s}
         del cols, kv, lws
 
+    # ---- router scoring over the production micro-batch (sequential by definition: one workgroup) ----
+    if args.stream_records > 0:
+        K_r, l_r = 256, 100
+        rng = np.random.default_rng(11)
+        cap_r = t32(rng.integers(120_000, 400_001, K_r))
+        win0 = t32(rng.integers(0, 100_000, K_r * l_r))
+        q0 = torch.from_numpy(rng.integers(0, 3000, K_r).astype(np.int64)).to(dev)
+        d0 = torch.from_numpy(rng.integers(0, 20000, K_r).astype(np.int64)).to(dev)
+        asg = torch.empty(n_req, dtype=torch.int32, device=dev)
+        sc = torch.empty(n_req, dtype=torch.int64, device=dev)
+        reps = 5
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(reps + 1):
+            if i == 1:
+                e0.record()
+            ps.ps_route(la_prompt, pred_t, K_r, l_r, win0.clone(), cap_r, q0.clone(), d0.clone(), asg, sc, status=status)
+        e1.record()
+        torch.cuda.synchronize()
+        route_s = e0.elapsed_time(e1) * 1e-3 / reps
+        out["router"] = {"requests": n_req, "instances": K_r, "window": l_r, "ms_per_batch": 1e3 * route_s,
+                         "requests_per_s": n_req / route_s, "us_per_request": 1e6 * route_s / n_req}
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = time_cpu_oracle(model_path, batch, ant)
     try:

@@ -193,6 +193,28 @@ int ps_scaler_scan(const int32_t* kv_tokens, const int32_t* capacity, int32_t n_
                    int32_t* over_count, int32_t* peak_tokens, int32_t* overloaded, int32_t* summary,
                    double* scale_down, void* hip_stream);
 
+/* Load-aware request router (Sec. 3.4.3): dispatch the n_req requests of a micro-batch one after the
+ * other, each to the instance with the smallest estimated load
+ *     L_i = (queued_p[i] + P) + (current_d[i] + D) + beta * max(0, U_i - T_mem) * M_i,
+ * U_i = the peak, over the next `window` iterations, of instance i's look-ahead map with the request
+ * virtually added (P + t tokens at iteration t < D), M_i = capacity[i].  Ties go to the lowest
+ * index.  After each decision the chosen instance's queued_p, current_d and window are updated, so
+ * the next request sees it.  Scores are integers: score100 = 100 L with T_mem as a whole percent.
+ *   prompt_tokens, pred_tokens  [n_req] int32 (P, D; a request with either negative is not dispatched:
+ *                  assigned = -1, PS_ST_BAD_RECORD)
+ *   window_tokens  [n_inst * window] int32, in/out: the first `window` slots of every instance's map
+ *   capacity       [n_inst] int32
+ *   queued_p, current_d  [n_inst] int64, in/out: tokens waiting to be prefilled / still to be decoded
+ *   assigned       [n_req] int32, out; score100 [n_req] int64, out: 100 L of the chosen instance
+ * All arrays are device pointers.  One workgroup walks the batch: n_inst <= 1024 and
+ * n_inst * (20 + 4 * window) bytes must fit a compute unit's LDS (PS_EUNSUPPORTED otherwise).
+ * The full-length maps are brought up to date by passing `assigned` as instance_id to
+ * ps_lookahead_update().  Errors: PS_EINVAL, PS_EUNSUPPORTED, PS_EHIP. */
+int ps_route(const int32_t* prompt_tokens, const int32_t* pred_tokens, int32_t n_req, int32_t n_inst,
+             int32_t window, int32_t* window_tokens, const int32_t* capacity, int64_t* queued_p,
+             int64_t* current_d, int32_t t_mem_pct, int32_t beta, int32_t* assigned, int64_t* score100,
+             ps_status* status, void* hip_stream);
+
 /* Kernel-family timing for benchmarks.  While enabled, ps_predict_load() brackets every kernel
  * launch with HIP events on the call's stream (the paper reports only the predictor's end-to-end
  * latency, Sec. 4.5; this splits it by kernel).  ps_profile_read() waits for `hip_stream`, adds

@@ -32,6 +32,9 @@ def route(prompt_tokens, pred_tokens, window_tokens, capacity, queued_p, current
     score = np.zeros(n, np.int64)
     for r in range(n):
         P, D = int(prompt_tokens[r]), int(pred_tokens[r])
+        if P < 0 or D < 0:                      # no such request (e.g. a failed prediction): not dispatched
+            assigned[r], score[r] = -1, 0
+            continue
         best, best_i = None, -1
         for i in range(K):
             peak = -2**62

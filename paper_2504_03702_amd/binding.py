@@ -22,7 +22,7 @@ PS_ST_BAD_TOKEN, PS_ST_BAD_LENGTH, PS_ST_NAN, PS_ST_BAD_RECORD, PS_ST_RANGE = 0x
 EXPORTS = ["ps_model_load", "ps_model_free", "ps_model_get_info", "ps_workspace_bytes", "ps_predict_load",
            "ps_anticipate_workspace_bytes", "ps_anticipate", "ps_status_read", "ps_strerror",
            "ps_profile_enable", "ps_profile_read", "ps_profile_clock",
-           "ps_lookahead_workspace_bytes", "ps_lookahead_update", "ps_scaler_scan"]
+           "ps_lookahead_workspace_bytes", "ps_lookahead_update", "ps_scaler_scan", "ps_route"]
 PS_FAMILIES = ["embed", "gemm", "attention", "layernorm", "head", "refine"]
 
 
@@ -73,6 +73,8 @@ def load_library() -> ctypes.CDLL:
     lib.ps_lookahead_update.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp, vp]
     lib.ps_scaler_scan.restype = ctypes.c_int
     lib.ps_scaler_scan.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.ps_route.restype = ctypes.c_int
+    lib.ps_route.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.ps_status_read.restype = ctypes.c_int
     lib.ps_status_read.argtypes = [vp, vp, ctypes.POINTER(ps_status)]
     lib.ps_profile_enable.restype = ctypes.c_int
@@ -239,6 +241,23 @@ def ps_scaler_scan(kv_tokens: torch.Tensor, capacity: torch.Tensor, n_inst: int,
         _ptr(peak_tokens, torch.int32, "peak_tokens"), _ptr(overloaded, torch.int32, "overloaded"),
         _ptr(summary, torch.int32, "summary"), _ptr(scale_down, torch.float64, "scale_down"), _stream()),
         "ps_scaler_scan")
+
+
+def ps_route(prompt_tokens: torch.Tensor, pred_tokens: torch.Tensor, n_inst: int, window: int,
+             window_tokens: Optional[torch.Tensor], capacity: torch.Tensor, queued_p: torch.Tensor,
+             current_d: torch.Tensor, assigned: torch.Tensor, score100: torch.Tensor, t_mem_pct: int = 80,
+             beta: int = 1, status: Optional[torch.Tensor] = None) -> None:
+    n = prompt_tokens.numel()
+    if pred_tokens.numel() != n or assigned.numel() != n or score100.numel() != n or capacity.numel() != n_inst or \
+            queued_p.numel() != n_inst or current_d.numel() != n_inst or \
+            (window_tokens is not None and window_tokens.numel() != n_inst * window):
+        raise ValueError("ps_route: array sizes do not match n_req / n_inst / window")
+    _check(load_library().ps_route(
+        _ptr(prompt_tokens, torch.int32, "prompt_tokens"), _ptr(pred_tokens, torch.int32, "pred_tokens"), n, n_inst,
+        window, _ptr(window_tokens, torch.int32, "window_tokens"), _ptr(capacity, torch.int32, "capacity"),
+        _ptr(queued_p, torch.int64, "queued_p"), _ptr(current_d, torch.int64, "current_d"), t_mem_pct, beta,
+        _ptr(assigned, torch.int32, "assigned"), _ptr(score100, torch.int64, "score100"),
+        _ptr(status, torch.int64, "status"), _stream()), "ps_route")
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:

@@ -44,3 +44,10 @@ def test_later_requests_see_earlier_decisions():
     # r0 -> 0 (tie). r1: instance 0 has queue 44 and peak 2*43; instance 1 is empty -> 1. r2: symmetric again -> 0
     assert a.tolist() == [0, 1, 0]
     assert s[0] == 100 * 44 + (100 * 43 - 80 * 50)
+
+
+def test_requests_without_a_prediction_are_not_dispatched():
+    win = np.zeros((2, 4), np.int64)
+    a, s, win2, qp, cd = orr.route([10, 10, -3], [5, -1, 5], win, [1000, 1000], [0, 0], [0, 0])
+    assert a.tolist() == [0, -1, -1] and s.tolist() == [1500, 0, 0]
+    assert qp.tolist() == [10, 0] and cd.tolist() == [5, 0]
