@@ -29,8 +29,8 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 # step), from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; profiles/production_gemm_traffic.txt)
 # scaled by what the same counters read for a 1 GiB elementwise copy (x2.0 and x1.0).  Valid only for
 # the kernel source it was measured on: reported as null once that file has changed.
-GEMM_TRAFFIC = {"source_sha256_16": "f42587646c088dd2", "workload": "production",
-                "fetch_bytes": 22.616e9, "write_bytes": 10.023e9}
+GEMM_TRAFFIC = {"source_sha256_16": "1ee8adf51da5bba1", "workload": "production",
+                "fetch_bytes": 23.178e9, "write_bytes": 9.963e9}
 
 
 def measured_gemm_traffic(workload: str):
@@ -62,12 +62,12 @@ WORKLOADS = {
 
 def encoder_flops(cfg, lengths):
     """Flops of the work one call asks of the GEMM and attention kernels, on real tokens.  In the last
-    layer only the first row of every request goes on to the head, so there the library runs the QKV
-    projection alone over all rows and attention for the first rows: that is what is counted (the
+    layer only the first row of every request goes on to the head, so there the library runs the key and
+    value projections alone over all rows and attention for the first rows: that is what is counted (the
     small per-request side GEMMs are left out)."""
     H, F, L = cfg.hidden, cfg.ffn, cfg.layers
     S = lengths.astype(np.float64) + cfg.n_soft
-    gemm = (L - 1) * S.sum() * (8.0 * H * H + 4.0 * H * F) + S.sum() * 6.0 * H * H
+    gemm = (L - 1) * S.sum() * (8.0 * H * H + 4.0 * H * F) + S.sum() * 4.0 * H * H
     attn = (L - 1) * 4.0 * H * (S ** 2).sum() + 4.0 * H * S.sum()
     return gemm, attn
 
@@ -222,7 +222,8 @@ def main() -> int:
         H, F, T, L = cfg.hidden, cfg.ffn, int(lengths.sum()), cfg.layers
         qkv_b = T * (2 * H + 6 * H) + 6 * H * H
         rest_b = T * (2 * H + 8 * H) + T * (2 * H + 2 * F) + T * (2 * F + 8 * H) + 2 * H * H + 4 * H * F
-        out["roofline"]["algorithmic_bytes"] = (L * qkv_b + (L - 1) * rest_b) / (4 * (L - 1) + 1)
+        kv_b = T * (2 * H + 4 * H) + 4 * H * H                  # last layer: keys and values only
+        out["roofline"]["algorithmic_bytes"] = ((L - 1) * (qkv_b + rest_b) + kv_b) / (4 * (L - 1) + 1)
         if core_ghz > 0:
             # the core clock the chip sustained inside the last GEMM launch (the published peak assumes
             # 2.4 GHz): achieved / (peak * clock / 2.4) is the matrix cores' utilisation at that clock

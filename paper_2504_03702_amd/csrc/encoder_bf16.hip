@@ -89,8 +89,19 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
         const ResidualSrc in = {ws.ya, ws.sa, sg, sbeta, nullptr, nullptr};
         const ResidualSrc mid = {ws.yb, ws.sb, w.ln1_g, w.ln1_b, nullptr, nullptr};
         const ResidualSrc mid_cls = {ws.yb, ws.sb, w.ln1_g, w.ln1_b, ws.row_start, ws.seq_len};
-        PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_QKV, x, (const bf16_t*)w.w_qkv, w.b_qkv, none, qk, vt,
-                                               ws.max_rows, 3 * H, H, H, qkv_rows, clk, s));
+        if (!last) {
+            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_QKV, x, (const bf16_t*)w.w_qkv, w.b_qkv, none, qk, vt,
+                                                   ws.max_rows, 3 * H, H, H, qkv_rows, clk, s));
+        } else {
+            // keys and values of all rows; queries of the requests' first rows only, by a side GEMM on
+            // those rows gathered into the (not yet used) first-row buffer
+            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_KV, x, (const bf16_t*)w.w_qkv + (size_t)H * H, w.b_qkv + H, none,
+                                                   qk, vt, ws.max_rows, 2 * H, H, H, qkv_rows, clk, s));
+            const ResidualSrc first_rows = {nullptr, nullptr, nullptr, nullptr, ws.row_start, ws.seq_len};
+            PS_TIMED(PS_FAM_REFINE, launch_cls_rows(m, n_req, ws, x, (bf16_t*)ws.cls_a, s));
+            PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_Q_MAPPED, (const bf16_t*)ws.cls_a, (const bf16_t*)w.w_qkv, w.b_qkv,
+                                                     first_rows, qk, nullptr, ws.cls_rows, H, H, H, n_req_dev, nullptr, s));
+        }
         PS_TIMED(PS_FAM_ATTENTION, launch_attention_bf16(m, n_req, ws, last, s));
         if (!last)
             PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, att, (const bf16_t*)w.w_o, w.b_o, in, ws.yb,

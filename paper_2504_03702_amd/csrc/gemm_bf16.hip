@@ -4,7 +4,8 @@
 //                                        contraction index contiguous; fp32 accumulation)
 //   epilogue: + bias[n], then one of: store | erf-GELU, store | + residual stream, store fp32 |
 //             QKV split (query and key columns to [rows][2H], value columns transposed to
-//             Vt[H][max_rows] so the attention kernel reads keys-contiguous value tiles).
+//             Vt[H][max_rows] so the attention kernel reads keys-contiguous value tiles), also as
+//             keys and values only, and as the queries of mapped rows only.
 //
 // One workgroup computes a BM x BN tile.  Per 64-deep k slice the A and W sub-tiles are brought
 // straight from global memory into LDS (global_load_lds, 16 bytes per lane, no register staging),
@@ -277,7 +278,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
         const int m0 = tm * BM, n0 = tn * BN;
         const int m_base = m0 + wm * WTM, n_base = n0 + wn * WTN;
 
-        if (EPI == EPI_QKV && n0 >= 2 * hidden) {
+        // first value column of this launch's W: after the query and key columns, or after the key columns
+        const int v_col0 = EPI == EPI_KV ? hidden : 2 * hidden;
+        if ((EPI == EPI_QKV || EPI == EPI_KV) && n0 >= v_col0) {
             // Value columns go to Vt[feature][row].  One 32 x 32 accumulator tile at a time is staged as
             // [32 features][32 rows]; the 16-byte chunks of a feature's rows are XOR-swizzled with the
             // feature index so the 128-byte-strided writes of the 32 lanes spread over the banks.
@@ -299,7 +302,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
                         const float4 hi = *(const float4*)(stg + c * 32 + 4 * ((2 * rg + 1) ^ (c & 7)));
                         const uint4 o = make_uint4(cvt_pk_bf16(lo.x, lo.y), cvt_pk_bf16(lo.z, lo.w),
                                                    cvt_pk_bf16(hi.x, hi.y), cvt_pk_bf16(hi.z, hi.w));
-                        *(uint4*)(Vt + (int64_t)(n_base - 2 * hidden + 32 * j + c) * vt_ld + m_base + 32 * i + 8 * rg) = o;
+                        *(uint4*)(Vt + (int64_t)(n_base - v_col0 + 32 * j + c) * vt_ld + m_base + 32 * i + 8 * rg) = o;
                     }
                 }
             }
@@ -393,7 +396,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
             const int cg = lane % LPR, r_in = lane / LPR;
             const int col = n_base + 8 * cg;
             const float4 b0 = *(const float4*)(bias + col), b1 = *(const float4*)(bias + col + 4);
-            const int64_t ldc = EPI == EPI_QKV ? 2 * (int64_t)hidden : EPI == EPI_GELU_SPLIT ? 2 * (int64_t)N : (int64_t)N;
+            const int64_t ldc = (EPI == EPI_QKV || EPI == EPI_KV || EPI == EPI_Q_MAPPED) ? 2 * (int64_t)hidden
+                                : EPI == EPI_GELU_SPLIT ? 2 * (int64_t)N : (int64_t)N;
+            const int c_col = col + (EPI == EPI_KV ? hidden : 0);   // key columns sit after the query columns
             bf16_t* C = (bf16_t*)Cv;
 #pragma unroll
             for (int i = 0; i < T::TM; ++i)
@@ -403,7 +408,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
 #pragma unroll
                     for (int it = 0; it < NIT; ++it) {
                         const int r = r_in + RPI * it;
-                        const int64_t row = m_base + 32 * i + 8 * e4 + r;
+                        int64_t row = m_base + 32 * i + 8 * e4 + r;
+                        if (EPI == EPI_Q_MAPPED) {
+                            // GEMM row = request; its queries belong to the request's first row
+                            if (row >= rows || res.seq_len[row] <= 0) continue;
+                            row = res.row_map[row];
+                        }
                         const float4 lo = *(const float4*)(stg + r * SW + 8 * cg);
                         const float4 hi = *(const float4*)(stg + r * SW + 8 * cg + 4);
                         float v[8] = {lo.x + b0.x, lo.y + b0.y, lo.z + b0.z, lo.w + b0.w,
@@ -414,7 +424,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
                         }
                         const uint4 o = make_uint4(cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3]),
                                                    cvt_pk_bf16(v[4], v[5]), cvt_pk_bf16(v[6], v[7]));
-                        *(uint4*)(C + row * ldc + col) = o;
+                        *(uint4*)(C + row * ldc + c_col) = o;
                         if (EPI == EPI_GELU_SPLIT) {
                             // second half of the row: what the first rounding lost, as bf16 again
                             const uint32_t h[4] = {o.x, o.y, o.z, o.w};
@@ -423,7 +433,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
                             for (int t = 0; t < 4; ++t)
                                 l[t] = cvt_pk_bf16(v[2 * t] - __uint_as_float(h[t] << 16),
                                                    v[2 * t + 1] - __uint_as_float(h[t] & 0xffff0000u));
-                            *(uint4*)(C + row * ldc + N + col) = make_uint4(l[0], l[1], l[2], l[3]);
+                            *(uint4*)(C + row * ldc + N + c_col) = make_uint4(l[0], l[1], l[2], l[3]);
                         }
                     }
                 }
@@ -455,6 +465,8 @@ void launch_cfg(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float*
         case EPI_QKV: PS_LAUNCH(EPI_QKV); break;
         case EPI_GELU_SPLIT: PS_LAUNCH(EPI_GELU_SPLIT); break;
         case EPI_RESIDUAL_MAPPED: PS_LAUNCH(EPI_RESIDUAL_MAPPED); break;
+        case EPI_KV: PS_LAUNCH(EPI_KV); break;
+        case EPI_Q_MAPPED: PS_LAUNCH(EPI_Q_MAPPED); break;
     }
 #undef PS_LAUNCH
 }
@@ -469,7 +481,7 @@ void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const 
     // The per-request side problems that reduce to `hidden` columns have few tiles (one row per request,
     // few tile columns) and long contractions: 128 x 128 tiles give four times as many workgroups to
     // spread them over.
-    if (epi == EPI_RESIDUAL_MAPPED)
+    if (epi == EPI_RESIDUAL_MAPPED || epi == EPI_Q_MAPPED)
         launch_cfg<128, 128, 2, 2>(epi, A, W, bias, residual, C, vt, max_rows, N, K, hidden, total_rows, clk, s);
     else
         launch_cfg<256, 256, 2, 4>(epi, A, W, bias, residual, C, vt, max_rows, N, K, hidden, total_rows, clk, s);

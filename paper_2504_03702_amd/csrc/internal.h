@@ -96,7 +96,9 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
 enum GemmEpilogue {
     EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RESIDUAL = 2, EPI_QKV = 3,
     EPI_GELU_SPLIT = 4,          // GELU, then the fp32 value stored as two bf16 (value ~ hi + lo) in [rows][2N]
-    EPI_RESIDUAL_MAPPED = 5      // EPI_BIAS_RESIDUAL with GEMM row r living at stream row row_map[r]
+    EPI_RESIDUAL_MAPPED = 5,     // EPI_BIAS_RESIDUAL with GEMM row r living at stream row row_map[r]
+    EPI_KV = 6,                  // EPI_QKV without the query columns: W holds the key and value rows only
+    EPI_Q_MAPPED = 7             // query columns only, GEMM row r stored at row row_map[r] of the [rows][2H] buffer
 };
 // The residual stream entering a sublayer: LayerNorm(y) with the row statistics already known.
 struct ResidualSrc {
@@ -115,6 +117,8 @@ void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const 
                       int hidden, const int32_t* total_rows, int64_t* clk, hipStream_t s);
 void launch_cls_gather(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, const float2* stats,
                        const float* gamma, const float* beta, hipStream_t s);
+// out[r][0:hidden] = x[first row of request r] for every request (zeros for faulty ones and padding rows).
+void launch_cls_rows(const ps_model* m, int32_t n_req, const Workspace& ws, const bf16_t* x, bf16_t* out, hipStream_t s);
 // stats[first row of request r] = LayerNorm statistics of that row of y, for every request.
 void launch_cls_stats(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, float2* stats,
                       hipStream_t s);

@@ -303,7 +303,25 @@ __global__ __launch_bounds__(256) void cls_stats_kernel(const float* __restrict_
     if (lane == 0) stats[row] = make_float2(mean, rstd);
 }
 
+// The bf16 input rows of each request's first token, one per request, for the side GEMM that computes
+// only those rows' queries (last layer).  Rows of faulty requests and padding rows are zero.
+__global__ __launch_bounds__(256) void cls_rows_kernel(const bf16_t* __restrict__ x, int H, int n_req,
+                                                       const int32_t* __restrict__ seq_len,
+                                                       const int32_t* __restrict__ row_start, bf16_t* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    uint4* o = (uint4*)(out + (int64_t)r * H);
+    const bool live = r < n_req && seq_len[r] > 0;
+    const uint4* src = live ? (const uint4*)(x + (int64_t)row_start[r] * H) : nullptr;
+    for (int i = lane; i < H / 8; i += 64) o[i] = live ? src[i] : make_uint4(0u, 0u, 0u, 0u);
+}
+
 }  // namespace
+
+void launch_cls_rows(const ps_model* m, int32_t n_req, const Workspace& ws, const bf16_t* x, bf16_t* out, hipStream_t s) {
+    hipLaunchKernelGGL(cls_rows_kernel, dim3((unsigned)(ws.cls_rows / 4)), dim3(256), 0, s, x, m->info.hidden, n_req,
+                       ws.seq_len, ws.row_start, out);
+}
 
 void launch_cls_stats(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, float2* stats,
                       hipStream_t s) {
