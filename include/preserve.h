@@ -207,7 +207,7 @@ int ps_scaler_scan(const int32_t* kv_tokens, const int32_t* capacity, int32_t n_
  *   queued_p, current_d  [n_inst] int64, in/out: tokens waiting to be prefilled / still to be decoded
  *   assigned       [n_req] int32, out; score100 [n_req] int64, out: 100 L of the chosen instance
  * All arrays are device pointers.  One workgroup walks the batch: n_inst <= 1024 and
- * n_inst * (20 + 4 * window) bytes must fit a compute unit's LDS (PS_EUNSUPPORTED otherwise).
+ * n_inst * (20 + 4 * window) bytes plus 21 KB must fit in 160 KB of LDS (PS_EUNSUPPORTED otherwise).
  * The full-length maps are brought up to date by passing `assigned` as instance_id to
  * ps_lookahead_update().  Errors: PS_EINVAL, PS_EUNSUPPORTED, PS_EHIP. */
 int ps_route(const int32_t* prompt_tokens, const int32_t* pred_tokens, int32_t n_req, int32_t n_inst,

@@ -250,7 +250,7 @@ extern "C" int ps_scaler_scan(const int32_t* kv_tokens, const int32_t* capacity,
 namespace {
 
 const int kRouteThreads = 1024;
-const int kRouteLdsBytes = 150 * 1024;
+const int kRouteLdsBytes = 160 * 1024;       // all of a compute unit's LDS
 
 __global__ __launch_bounds__(kRouteThreads) void route_kernel(
     const int32_t* __restrict__ prompt_tokens, const int32_t* __restrict__ pred_tokens, int n_req, int n_inst,
@@ -260,10 +260,15 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(
     extern __shared__ __align__(16) unsigned char lds_raw[];
     long long* s_qp = (long long*)lds_raw;                       // [n_inst]
     long long* s_cd = s_qp + n_inst;                             // [n_inst]
-    long long* s_best = s_cd + n_inst;                           // [16] per-wavefront minimum score
-    int* s_best_i = (int*)(s_best + 16);                         // [16] and its instance
-    int* s_cap = s_best_i + 16;                                  // [n_inst]
-    int* s_win = s_cap + n_inst;                                 // [n_inst][window]
+    long long* s_best = s_cd + n_inst;                           // [2][16] per-wavefront minimum score
+    int* s_best_i = (int*)(s_best + 32);                         // [2][16] and its instance
+    int* s_cap = s_best_i + 32;                                  // [n_inst]
+    int2* s_req = (int2*)(s_cap + n_inst + (n_inst & 1));         // [1024] (P, D) of the requests being walked
+    long long* s_out_s = (long long*)(s_req + kRouteThreads);    // [1024] their scores
+    int* s_out_i = (int*)(s_out_s + kRouteThreads);              // [1024] and instances, written out per chunk: a
+                                                                 // global store per request would be waited for at
+                                                                 // every barrier
+    int* s_win = s_out_i + kRouteThreads;                        // [n_inst][window]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int i = tid; i < n_inst; i += kRouteThreads) { s_qp[i] = queued_p[i]; s_cd[i] = current_d[i]; s_cap[i] = capacity[i]; }
     for (int i = tid; i < n_inst * window; i += kRouteThreads) s_win[i] = window_tokens[i];
@@ -274,9 +279,19 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(
     const long long kNone = 0x7fffffffffffffffll;
     bool range_fault = false;
     for (int r = 0; r < n_req; ++r) {
-        const int P = prompt_tokens[r], D = pred_tokens[r];     // uniform
+        if ((r & (kRouteThreads - 1)) == 0) {
+            // results of the last 1024 requests out, the next 1024 requests in
+            __syncthreads();
+            if (r > 0) { assigned[r - kRouteThreads + tid] = s_out_i[tid]; score100[r - kRouteThreads + tid] = s_out_s[tid]; }
+            if (r + tid < n_req) s_req[tid] = make_int2(prompt_tokens[r + tid], pred_tokens[r + tid]);
+            __syncthreads();
+        }
+        const int slot = r & (kRouteThreads - 1);
+        const int2 pd = s_req[slot];
+        const int P = pd.x, D = pd.y;                           // uniform
         if (P < 0 || D < 0) {
-            if (tid == 0) { assigned[r] = -1; score100[r] = 0; report_fault(st, PS_ST_BAD_RECORD, r); }
+            if (tid == 0) { s_out_i[slot] = -1; s_out_s[slot] = 0; report_fault(st, PS_ST_BAD_RECORD, r); }
+            __syncthreads();                                    // keeps the one-barrier-per-request rhythm of the exchange slots
             continue;
         }
         long long peak = -kNone;
@@ -295,16 +310,19 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(
             const int oi = __shfl_xor(bi, o, 64);
             if (oL < L || (oL == L && oi < bi)) { L = oL; bi = oi; }
         }
-        if (lane == 0) { s_best[wave] = L; s_best_i[wave] = bi; }
+        // the exchange slots alternate between requests, so one barrier per request is enough: a slot
+        // is rewritten two requests later, after the barrier of the request in between
+        const int par = (r & 1) * 16;
+        if (lane == 0) { s_best[par + wave] = L; s_best_i[par + wave] = bi; }
         __syncthreads();
-        long long bL = s_best[0];
-        int bI = s_best_i[0];
+        long long bL = s_best[par];
+        int bI = s_best_i[par];
         for (int w = 1; w < kRouteThreads / 64; ++w) {
-            const long long oL = s_best[w];
-            const int oi = s_best_i[w];
+            const long long oL = s_best[par + w];
+            const int oi = s_best_i[par + w];
             if (oL < bL || (oL == bL && oi < bI)) { bL = oL; bI = oi; }
         }
-        if (tid == 0) { assigned[r] = bI; score100[r] = bL; }
+        if (tid == 0) { s_out_i[slot] = bI; s_out_s[slot] = bL; }
         if (mine && inst == bI) {
             const int stop = min(D, window);
             for (int t = sub; t < stop; t += tpi) {
@@ -314,7 +332,12 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(
             }
             if (sub == 0) { s_qp[inst] += P; s_cd[inst] += D; }
         }
-        __syncthreads();                                        // the per-wavefront slots are reused next round
+        // no barrier here: an instance's window and counters are only ever touched by its own threads
+    }
+    __syncthreads();
+    {   // results of the last, possibly partial, chunk
+        const int done = n_req & ~(kRouteThreads - 1), first = done == n_req ? n_req - kRouteThreads : done;
+        if (first + tid < n_req) { assigned[first + tid] = s_out_i[tid]; score100[first + tid] = s_out_s[tid]; }
     }
     if (range_fault) report_fault(st, PS_ST_RANGE, -1);
     for (int i = tid; i < n_inst; i += kRouteThreads) { queued_p[i] = s_qp[i]; current_d[i] = s_cd[i]; }
@@ -332,7 +355,7 @@ extern "C" int ps_route(const int32_t* prompt_tokens, const int32_t* pred_tokens
     if (n_req == 0) return PS_OK;
     if (!prompt_tokens || !pred_tokens || !assigned || !score100) return PS_EINVAL;
     if (n_inst > kRouteThreads) return PS_EUNSUPPORTED;
-    const size_t lds = (size_t)n_inst * 20 + 16 * 12 + (size_t)n_inst * window * 4 + 64;
+    const size_t lds = (size_t)n_inst * 20 + 32 * 12 + 20 * (size_t)kRouteThreads + (size_t)n_inst * window * 4 + 64;
     if (lds > (size_t)kRouteLdsBytes) return PS_EUNSUPPORTED;
     int tpi = 64;                                               // threads per instance: a power of two, <= 64
     while (tpi > 1 && (int64_t)tpi * n_inst > kRouteThreads) tpi >>= 1;
