@@ -87,7 +87,7 @@ def time_cpu_oracle(model_path, batch, ant, budget_s=15.0):
     H, F, L = model["hidden"], model["ffn"], model["layers"]
     lengths = batch.valid_lengths()
     per_req = L * (lengths * (8.0 * H * H + 4.0 * H * F) + 4.0 * H * lengths.astype(np.float64) ** 2)
-    n = int(np.searchsorted(np.cumsum(per_req), 0.5 * rate * budget_s)) + 1     # oracle runs at about half the probe rate
+    n = int(np.searchsorted(np.cumsum(per_req), 0.25 * rate * budget_s)) + 1    # the oracle runs at about a quarter of the probe rate
     n = max(1, min(n, batch.n_req))
     offs = batch.offsets[: n + 1]
     lens = None if batch.lengths is None else batch.lengths[:n]
