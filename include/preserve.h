@@ -215,6 +215,25 @@ int ps_route(const int32_t* prompt_tokens, const int32_t* pred_tokens, int32_t n
              int64_t* current_d, int32_t t_mem_pct, int32_t beta, int32_t* assigned, int64_t* score100,
              ps_status* status, void* hip_stream);
 
+/* Online phase of the service workload predictor (Sec. 3.2, Alg. 2).  For each of n_services services
+ * two multiplicative LSTMs (Krause et al. 2016), one for prompt tokens and one for response tokens,
+ * forecast the token count of the current time window from the counts of the k past windows, then,
+ * with that forecast appended to the history, the count of the next window; the next window's
+ * counts give the number of instances  N = max(P / mu_p, D / mu_d, (P + D) / mu_t).
+ *   weights  [n_services][2][5 H^2 + 10 H + 2] float, H = hidden <= 64; per model, in this order:
+ *            w_mx[H] W_mh[H][H] w_hx[H] W_hm[H][H] b_h[H] w_ix[H] W_im[H][H] b_i[H] w_ox[H] W_om[H][H]
+ *            b_o[H] w_fx[H] W_fm[H][H] b_f[H] w_out[H] b_out scale, for the recurrence
+ *              m = (w_mx x) * (W_mh h),  hh = w_hx x + W_hm m + b_h,  i, o, f = sigmoid(w_.x x + W_.m m + b_.),
+ *              c = f c + i tanh(hh),  h = tanh(c) o;   x = count / scale;  forecast = max(0, scale (w_out . h + b_out))
+ *            model 0 of a service is the prompt-token model, model 1 the response-token model
+ *   hist_p, hist_d  [n_services][k] float: token counts of the k past windows, oldest first
+ *   mu       [n_services][3] float: one instance's prefill, decode and total token capacity per window
+ *   out      [n_services][5] float: forecasts (P current, D current, P next, D next) and N (not rounded)
+ * All arrays are device pointers; fp32 arithmetic.  Errors: PS_EINVAL, PS_EUNSUPPORTED (hidden above
+ * 64), PS_EHIP. */
+int ps_forecast(const float* weights, int32_t hidden, const float* hist_p, const float* hist_d,
+                int32_t n_services, int32_t k, const float* mu, float* out, void* hip_stream);
+
 /* Kernel-family timing for benchmarks.  While enabled, ps_predict_load() brackets every kernel
  * launch with HIP events on the call's stream (the paper reports only the predictor's end-to-end
  * latency, Sec. 4.5; this splits it by kernel).  ps_profile_read() waits for `hip_stream`, adds

@@ -22,7 +22,7 @@ PS_ST_BAD_TOKEN, PS_ST_BAD_LENGTH, PS_ST_NAN, PS_ST_BAD_RECORD, PS_ST_RANGE = 0x
 EXPORTS = ["ps_model_load", "ps_model_free", "ps_model_get_info", "ps_workspace_bytes", "ps_predict_load",
            "ps_anticipate_workspace_bytes", "ps_anticipate", "ps_status_read", "ps_strerror",
            "ps_profile_enable", "ps_profile_read", "ps_profile_clock",
-           "ps_lookahead_workspace_bytes", "ps_lookahead_update", "ps_scaler_scan", "ps_route"]
+           "ps_lookahead_workspace_bytes", "ps_lookahead_update", "ps_scaler_scan", "ps_route", "ps_forecast"]
 PS_FAMILIES = ["embed", "gemm", "attention", "layernorm", "head", "refine"]
 
 
@@ -75,6 +75,8 @@ def load_library() -> ctypes.CDLL:
     lib.ps_scaler_scan.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.ps_route.restype = ctypes.c_int
     lib.ps_route.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.ps_forecast.restype = ctypes.c_int
+    lib.ps_forecast.argtypes = [vp, i32, vp, vp, i32, i32, vp, vp, vp]
     lib.ps_status_read.restype = ctypes.c_int
     lib.ps_status_read.argtypes = [vp, vp, ctypes.POINTER(ps_status)]
     lib.ps_profile_enable.restype = ctypes.c_int
@@ -258,6 +260,17 @@ def ps_route(prompt_tokens: torch.Tensor, pred_tokens: torch.Tensor, n_inst: int
         _ptr(queued_p, torch.int64, "queued_p"), _ptr(current_d, torch.int64, "current_d"), t_mem_pct, beta,
         _ptr(assigned, torch.int32, "assigned"), _ptr(score100, torch.int64, "score100"),
         _ptr(status, torch.int64, "status"), _stream()), "ps_route")
+
+
+def ps_forecast(weights: torch.Tensor, hidden: int, hist_p: torch.Tensor, hist_d: torch.Tensor, n_services: int,
+                k: int, mu: torch.Tensor, out: torch.Tensor) -> None:
+    if weights.numel() != n_services * 2 * (5 * hidden * hidden + 10 * hidden + 2) or hist_p.numel() != n_services * k or \
+            hist_d.numel() != n_services * k or mu.numel() != 3 * n_services or out.numel() != 5 * n_services:
+        raise ValueError("ps_forecast: array sizes do not match n_services / hidden / k")
+    _check(load_library().ps_forecast(
+        _ptr(weights, torch.float32, "weights"), hidden, _ptr(hist_p, torch.float32, "hist_p"),
+        _ptr(hist_d, torch.float32, "hist_d"), n_services, k, _ptr(mu, torch.float32, "mu"),
+        _ptr(out, torch.float32, "out"), _stream()), "ps_forecast")
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:

@@ -360,3 +360,59 @@ def make_lookahead_inputs(kind: str, seed: int = 0, n: Optional[int] = None,
     capacity = rng.integers(120_000, 400_001, n_inst).astype(np.int32)
     return LookaheadInputs(*[np.ascontiguousarray(rec[:, c]) for c in range(6)], capacity, n_inst, map_len)
 
+
+
+FORECASTER_FIELDS = ("w_mx", "W_mh", "w_hx", "W_hm", "b_h", "w_ix", "W_im", "b_i", "w_ox", "W_om", "b_o", "w_fx", "W_fm",
+                     "b_f", "w_out", "b_out", "scale")
+
+
+@dataclasses.dataclass
+class ForecasterInputs:
+    """Models and histories of the service workload predictor (paper Sec. 3.2)."""
+    weights: np.ndarray           # [n_services, 2, 5 H^2 + 10 H + 2] float32, fields in FORECASTER_FIELDS order
+    hist_p: np.ndarray            # [n_services, k] float32 prompt tokens per past window
+    hist_d: np.ndarray            # [n_services, k] float32 response tokens per past window
+    mu: np.ndarray                # [n_services, 3] float32 per-instance capacities (prefill, decode, total)
+    hidden: int
+    k: int
+
+    def model(self, s: int, kind: int) -> dict:
+        """Model `kind` (0 prompt, 1 response) of service s as named float64 arrays."""
+        H, flat, at, out = self.hidden, self.weights[s, kind].astype(np.float64), 0, {}
+        for n in FORECASTER_FIELDS:
+            size = H * H if n.startswith("W_") else 1 if n in ("b_out", "scale") else H
+            v = flat[at:at + size]
+            out[n] = v.reshape(H, H) if n.startswith("W_") else v[0] if size == 1 and n in ("b_out", "scale") else v
+            at += size
+        return out
+
+
+def make_forecaster_inputs(seed: int = 0, n_services: int = 8, hidden: int = 32, k: int = 12) -> ForecasterInputs:
+    """Random-init models (N(0, 0.3) matrices, N(0, 0.5) vectors, readout bias 0.5) and histories shaped
+    like the paper's traces: token counts per 10-minute window following a daily cycle with noise,
+    prompt tokens around 4e6 and response tokens around 2e6 per window, scaled by 1e7 inside the model."""
+    rng = np.random.default_rng(seed + 7000)
+    H = hidden
+    per_model = 5 * H * H + 10 * H + 2
+    w = np.zeros((n_services, 2, per_model), np.float32)
+    for s in range(n_services):
+        for kind in range(2):
+            parts = []
+            for n in FORECASTER_FIELDS:
+                if n.startswith("W_"):
+                    parts.append(rng.normal(0, 0.3, H * H))
+                elif n == "b_out":
+                    parts.append(np.array([0.5]))
+                elif n == "scale":
+                    parts.append(np.array([1e7]))
+                else:
+                    parts.append(rng.normal(0, 0.5, H))
+            w[s, kind] = np.concatenate(parts).astype(np.float32)
+    t = np.arange(k)[None, :] + rng.integers(0, 144, (n_services, 1))
+    cycle = 1.0 + 0.5 * np.sin(2 * np.pi * t / 144.0)
+    hist_p = (4e6 * cycle * rng.uniform(0.8, 1.2, (n_services, k))).astype(np.float32)
+    hist_d = (2e6 * cycle * rng.uniform(0.8, 1.2, (n_services, k))).astype(np.float32)
+    mu = np.stack([rng.uniform(0.8e6, 1.6e6, n_services), rng.uniform(0.3e6, 0.8e6, n_services),
+                   rng.uniform(1.0e6, 2.0e6, n_services)], 1).astype(np.float32)
+    return ForecasterInputs(w, hist_p, hist_d, mu, hidden, k)
+
