@@ -65,6 +65,13 @@ void transpose_into(T* dst, int64_t dst_ld, const T* src, int K, int N) {
                 for (int n = n0; n < n0 + B && n < N; ++n) dst[(int64_t)n * dst_ld + k] = src[(int64_t)k * N + n];
 }
 
+inline bf16_t float_to_bf16(float f) {      // round to nearest even; the weights hold no NaN worth keeping
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
 // Multiply a bf16 value by 2^-3 exactly (head size 64: 1/sqrt(64)); subnormal results flush
 // towards zero by at most one unit of the smallest bf16 exponent, which N(0, 0.02)-scale
 // weights never reach; zero stays zero.
@@ -107,6 +114,7 @@ Workspace plan_workspace(const ps_model_info& info, int64_t n_tokens, int32_t n_
         ws.yb = (float*)take(4 * rows * H);
         ws.sa = (float2*)take(8 * rows);
         ws.sb = (float2*)take(8 * rows);
+        ws.ps = (float2*)take(8 * rows * (H / 64));
         ws.cls_rows = (int64_t)align_up((size_t)(n_req > 0 ? n_req : 1), PS_ROW_TILE);
         ws.cls_a = take(2 * ws.cls_rows * 2 * H);
         ws.cls_g = take(2 * ws.cls_rows * 2 * F);
@@ -185,7 +193,7 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
     // Two passes over the same carving code: first sizes, then fills the staging buffer.
     std::vector<uint8_t> stage;
     size_t o_etok = 0, o_epos = 0, o_esoft = 0, o_lneg = 0, o_lneb = 0, o_h1 = 0, o_bh1 = 0, o_wh2 = 0;
-    struct LayerOff { size_t wqkv, wo, w1, w2, wod, w1d, w2d, bqkv, bo, b1, b2, g1, be1, g2, be2; };
+    struct LayerOff { size_t wqkv, wo, w1, w2, wod, w1d, w2d, bqkv, bo, b1, b2, g1, be1, g2, be2, cqkv, c1, d1; };
     std::vector<LayerOff> lo((size_t)L);
     for (int pass = 0; pass < 2; ++pass) {
         Carver c;
@@ -211,6 +219,29 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
         o_esoft = put_raw((size_t)M * H);
         o_lneg = put_f32(H);
         o_lneb = put_f32(H);
+        // Fold the LayerNorm (gamma, beta) in front of a bf16 map W [N][K] with bias b into it: W becomes
+        // gamma W (rounded to bf16 again), c its column sums over the rounded values, d = b + beta W.
+        auto fold_layernorm = [&](size_t w_at, int64_t N, int64_t K, size_t gamma_at, size_t beta_at, size_t b_at,
+                                  size_t c_at, size_t d_at) {
+            bf16_t* w = (bf16_t*)(stage.data() + w_at);
+            const float* gamma = (const float*)(stage.data() + gamma_at);
+            const float* beta = (const float*)(stage.data() + beta_at);
+            const float* b = (const float*)(stage.data() + b_at);
+            float* cs = (float*)(stage.data() + c_at);
+            float* ds = (float*)(stage.data() + d_at);
+            for (int64_t n = 0; n < N; ++n) {
+                double c = 0.0, d = 0.0;
+                for (int64_t k = 0; k < K; ++k) {
+                    const float wv = bf16_to_float(w[n * K + k]);
+                    d += (double)beta[k] * wv;
+                    const bf16_t folded = float_to_bf16(gamma[k] * wv);
+                    w[n * K + k] = folded;
+                    c += bf16_to_float(folded);
+                }
+                cs[n] = (float)c;
+                ds[n] = (float)((double)b[n] + d);
+            }
+        };
         for (int64_t l = 0; l < L; ++l) {
             LayerOff& t = lo[(size_t)l];
             // W_q b_q W_k b_k W_v b_v come one after the other; they become one [*, 3H] map.
@@ -236,6 +267,14 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
                     for (int64_t i = 0; i < H; ++i)
                         memcpy(dst + i * 3 * H + part * H, src + i * H, (size_t)H * 4);
                 }
+            }
+            if (info.dtype == 1) {
+                // the LayerNorm in front of the QKV map: the embedding's for the first layer, else the
+                // previous layer's second one; d replaces the bias in place
+                t.cqkv = c.take((size_t)3 * H * 4);
+                if (pass)
+                    fold_layernorm(t.wqkv, 3 * H, H, l ? lo[(size_t)l - 1].g2 : o_lneg, l ? lo[(size_t)l - 1].be2 : o_lneb,
+                                   t.bqkv, t.cqkv, t.bqkv);
             }
             auto put_matrix = [&](int64_t K, int64_t N) {   // file [K][N]
                 size_t at = c.take((size_t)K * N * fe);
@@ -269,6 +308,12 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
             t.w1 = put_matrix(H, F);
             t.w1d = put_doubled(t.w1, H, F);
             t.b1 = put_f32(F);
+            if (info.dtype == 1) {
+                // the first LayerNorm goes into W_1 (after the plain copy for the first-row pass was taken)
+                t.c1 = c.take((size_t)F * 4);
+                t.d1 = c.take((size_t)F * 4);
+                if (pass) fold_layernorm(t.w1, F, H, t.g1, t.be1, t.b1, t.c1, t.d1);
+            }
             t.w2 = put_matrix(F, H);
             t.w2d = put_doubled(t.w2, F, H);
             t.b2 = put_f32(H);
@@ -321,6 +366,7 @@ extern "C" int ps_model_load(const char* path, int device, ps_model** out) {
         w.b_1 = (float*)(b + t.b1); w.b_2 = (float*)(b + t.b2);
         w.ln1_g = (float*)(b + t.g1); w.ln1_b = (float*)(b + t.be1);
         w.ln2_g = (float*)(b + t.g2); w.ln2_b = (float*)(b + t.be2);
+        w.c_qkv = (float*)(b + t.cqkv); w.c_1 = (float*)(b + t.c1); w.d_1 = (float*)(b + t.d1);
     }
     m->w_h1t = (float*)(b + o_h1);
     m->b_h1 = (float*)(b + o_bh1);

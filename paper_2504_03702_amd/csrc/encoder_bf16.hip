@@ -1,69 +1,44 @@
-// bf16 encoder path: the per-layer sequence of MFMA GEMMs, attention and LayerNorm launches, and
-// the row LayerNorm kernel.
+// bf16 encoder path: the per-layer sequence of MFMA GEMMs and attention launches.  There is no
+// LayerNorm kernel: a residual epilogue writes the new sums in fp32 (the residual stream), as bf16
+// (the next map's operand) and as per-row partial sums; a small kernel turns those into (mean, 1/std),
+// and the next map, which carries the LayerNorm's scale and shift in its weights, finishes the
+// normalisation in its own epilogue.
 #include "device_util.h"
 #include "internal.h"
 
 namespace {
 
-// LayerNorm of one row of fp32 sums per wavefront (biased variance): writes the bf16 row the
-// next GEMM reads and the row's (mean, 1/std), from which later epilogues recompute the fp32
-// LayerNorm output.  A row is H = 256 * NCH floats; lane l holds the 4-element chunks l, l + 64, ...
-// so every load and store of a wavefront is one contiguous run.
-template <int NCH>
-__global__ __launch_bounds__(256) void layernorm_bf16_kernel(const float* __restrict__ y, bf16_t* __restrict__ x,
-                                                             float2* __restrict__ stats,
-                                                             const float* __restrict__ gamma,
-                                                             const float* __restrict__ beta, float eps,
-                                                             const int32_t* __restrict__ total_rows) {
-    constexpr int H = 256 * NCH;
-    const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= *total_rows) return;
-    const float4* src = (const float4*)(y + row * H);
-    float4 v[NCH];
-    float sum = 0.f;
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        v[c] = src[lane + 64 * c];
-        sum += (v[c].x + v[c].y) + (v[c].z + v[c].w);
+// Row statistics from the partial sums the residual epilogues leave: 16 lanes per row, lane p taking
+// the pieces p, p + 16, ...; the 16 partial results are added in a fixed order.  Biased variance as
+// E[v^2] - mean^2 (the rows are residual-stream sums, whose mean is small against their spread).
+__global__ __launch_bounds__(256) void ln_stats_kernel(const float2* __restrict__ pstats, float2* __restrict__ stats,
+                                                       int pieces, float inv_n, float eps,
+                                                       const int32_t* __restrict__ total_rows) {
+    const int p = threadIdx.x & 15;
+    const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    if (row >= *total_rows) return;                     // whole 16-lane groups leave together
+    float sm = 0.f, sq = 0.f;
+    for (int c = p; c < pieces; c += 16) {
+        const float2 v = pstats[row * pieces + c];
+        sm += v.x;
+        sq += v.y;
     }
-    const float mean = wave_sum(sum) * (1.0f / H);
-    float sq = 0.f;
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        v[c].x -= mean; v[c].y -= mean; v[c].z -= mean; v[c].w -= mean;
-        sq = fmaf(v[c].x, v[c].x, sq); sq = fmaf(v[c].y, v[c].y, sq);
-        sq = fmaf(v[c].z, v[c].z, sq); sq = fmaf(v[c].w, v[c].w, sq);
+    for (int o = 1; o < 16; o <<= 1) {
+        sm += __shfl_xor(sm, o, 16);
+        sq += __shfl_xor(sq, o, 16);
     }
-    const float rstd = 1.0f / sqrtf(wave_sum(sq) * (1.0f / H) + eps);
-    if (lane == 0) stats[row] = make_float2(mean, rstd);
-    uint2* dst = (uint2*)(x + row * H);
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        const float4 g = ((const float4*)gamma)[lane + 64 * c];
-        const float4 b = ((const float4*)beta)[lane + 64 * c];
-        dst[lane + 64 * c] = make_uint2(pack_bf16x2(v[c].x * rstd * g.x + b.x, v[c].y * rstd * g.y + b.y),
-                                        pack_bf16x2(v[c].z * rstd * g.z + b.z, v[c].w * rstd * g.w + b.w));
-    }
+    const float mean = sm * inv_n;
+    const float var = fmaxf(sq * inv_n - mean * mean, 0.f);
+    if (p == 0) stats[row] = make_float2(mean, 1.0f / sqrtf(var + eps));
 }
 
 }  // namespace
 
-void launch_layernorm_bf16(const float* y, bf16_t* x, float2* stats, const float* gamma, const float* beta,
-                           float eps, int hidden, int64_t max_rows, const int32_t* total_rows, hipStream_t s) {
-    const dim3 grid((unsigned)(max_rows / 4)), block(256);
-#define PS_LN(N) hipLaunchKernelGGL(layernorm_bf16_kernel<N>, grid, block, 0, s, y, x, stats, gamma, beta, eps, total_rows)
-    switch (hidden / 256) {
-        case 1: PS_LN(1); break;
-        case 2: PS_LN(2); break;
-        case 3: PS_LN(3); break;
-        case 4: PS_LN(4); break;
-        case 5: PS_LN(5); break;
-        case 6: PS_LN(6); break;
-        case 7: PS_LN(7); break;
-        case 8: PS_LN(8); break;
-    }
-#undef PS_LN
+void launch_ln_stats(const float2* pstats, float2* stats, float eps, int hidden, int64_t max_rows,
+                     const int32_t* total_rows, hipStream_t s) {
+    hipLaunchKernelGGL(ln_stats_kernel, dim3((unsigned)(max_rows / 16)), dim3(256), 0, s, pstats, stats, hidden / 64,
+                       1.0f / (float)hidden, eps, total_rows);
 }
 
 void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hipStream_t s) {
@@ -73,7 +48,7 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
            *x1 = (bf16_t*)ws.x1, *g = (bf16_t*)ws.g;
     const int32_t* rows = &ws.meta->total_rows;        // the rows that belong to requests
     const int32_t* qkv_rows = &ws.meta->qkv_rows;     // QKV projection: those plus the slack the key tiles read
-    const ResidualSrc none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    const ResidualSrc none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     const int32_t* n_req_dev = &ws.meta->n_req;
     int64_t* clk = m->profiling ? m->clk_slot : nullptr;   // clock probe of the large GEMMs
     // the stream entering layer 0 is the embedding LayerNorm of the sums the embed kernel left in ya
@@ -86,18 +61,27 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
         // all-row GEMMs and LayerNorms are skipped, attention computes the first rows only, and the
         // per-request side pass below, which every layer runs for accuracy, is all that is left.
         const bool last = l + 1 == f.layers;
-        const ResidualSrc in = {ws.ya, ws.sa, sg, sbeta, nullptr, nullptr};
-        const ResidualSrc mid = {ws.yb, ws.sb, w.ln1_g, w.ln1_b, nullptr, nullptr};
-        const ResidualSrc mid_cls = {ws.yb, ws.sb, w.ln1_g, w.ln1_b, ws.row_start, ws.seq_len};
+        // what the stream's new sums also leave behind unless this is the last layer: the bf16 operand of
+        // the next map (x1 for the feed-forward block, x for the next layer) and the partial statistics
+        bf16_t* x1_out = last ? nullptr : x1;
+        bf16_t* x_out = last ? nullptr : x;
+        float2* ps = last ? nullptr : ws.ps;
+        const ResidualSrc in = {ws.ya, ws.sa, sg, sbeta, nullptr, nullptr, x1_out, ps, nullptr};
+        const ResidualSrc mid = {ws.yb, ws.sb, w.ln1_g, w.ln1_b, nullptr, nullptr, x_out, ps, nullptr};
+        const ResidualSrc mid_cls = {ws.yb, ws.sb, w.ln1_g, w.ln1_b, ws.row_start, ws.seq_len, x_out, ps, nullptr};
+        // operands of the maps with a folded LayerNorm: row statistics and column sums
+        const ResidualSrc fold_qkv = {nullptr, ws.sa, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.c_qkv};
+        const ResidualSrc fold_1 = {nullptr, ws.sb, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.c_1};
         if (!last) {
-            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_QKV, x, (const bf16_t*)w.w_qkv, w.b_qkv, none, qk, vt,
+            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_QKV, x, (const bf16_t*)w.w_qkv, w.b_qkv, fold_qkv, qk, vt,
                                                    ws.max_rows, 3 * H, H, H, qkv_rows, clk, s));
         } else {
             // keys and values of all rows; queries of the requests' first rows only, by a side GEMM on
             // those rows gathered into the (not yet used) first-row buffer
-            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_KV, x, (const bf16_t*)w.w_qkv + (size_t)H * H, w.b_qkv + H, none,
+            const ResidualSrc fold_kv = {nullptr, ws.sa, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.c_qkv + H};
+            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_KV, x, (const bf16_t*)w.w_qkv + (size_t)H * H, w.b_qkv + H, fold_kv,
                                                    qk, vt, ws.max_rows, 2 * H, H, H, qkv_rows, clk, s));
-            const ResidualSrc first_rows = {nullptr, nullptr, nullptr, nullptr, ws.row_start, ws.seq_len};
+            const ResidualSrc first_rows = {nullptr, ws.sa, nullptr, nullptr, ws.row_start, ws.seq_len, nullptr, nullptr, w.c_qkv};
             PS_TIMED(PS_FAM_REFINE, launch_cls_rows(m, n_req, ws, x, (bf16_t*)ws.cls_a, s));
             PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_Q_MAPPED, (const bf16_t*)ws.cls_a, (const bf16_t*)w.w_qkv, w.b_qkv,
                                                      first_rows, qk, nullptr, ws.cls_rows, H, H, H, n_req_dev, nullptr, s));
@@ -108,13 +92,12 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
                                                    nullptr, ws.max_rows, H, H, H, rows, clk, s));
         // output projection again for each request's first row from the hi | lo pairs the attention
         // kernel left in cls_a (see the feed-forward refinement below)
-        const ResidualSrc in_cls = {ws.ya, ws.sa, sg, sbeta, ws.row_start, ws.seq_len};
+        const ResidualSrc in_cls = {ws.ya, ws.sa, sg, sbeta, ws.row_start, ws.seq_len, x1_out, ps, nullptr};
         PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_RESIDUAL_MAPPED, (const bf16_t*)ws.cls_a, (const bf16_t*)w.w_od,
                                                  w.b_o, in_cls, ws.yb, nullptr, ws.cls_rows, H, 2 * H, H, n_req_dev, nullptr, s));
         if (!last) {
-            PS_TIMED(PS_FAM_LAYERNORM, launch_layernorm_bf16(ws.yb, x1, ws.sb, w.ln1_g, w.ln1_b, m->ln_eps, H,
-                                                             ws.max_rows, rows, s));
-            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_GELU, x1, (const bf16_t*)w.w_1, w.b_1, none, g, nullptr,
+            PS_TIMED(PS_FAM_LAYERNORM, launch_ln_stats(ws.ps, ws.sb, m->ln_eps, H, ws.max_rows, rows, s));
+            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_GELU, x1, (const bf16_t*)w.w_1, w.d_1, fold_1, g, nullptr,
                                                    ws.max_rows, F, H, H, rows, clk, s));
             PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, g, (const bf16_t*)w.w_2, w.b_2, mid, ws.ya,
                                                    nullptr, ws.max_rows, H, F, H, rows, clk, s));
@@ -131,8 +114,7 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
         PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_RESIDUAL_MAPPED, (const bf16_t*)ws.cls_g, (const bf16_t*)w.w_2d,
                                                  w.b_2, mid_cls, ws.ya, nullptr, ws.cls_rows, H, 2 * F, H, n_req_dev, nullptr, s));
         if (!last)
-            PS_TIMED(PS_FAM_LAYERNORM, launch_layernorm_bf16(ws.ya, x, ws.sa, w.ln2_g, w.ln2_b, m->ln_eps, H,
-                                                             ws.max_rows, rows, s));
+            PS_TIMED(PS_FAM_LAYERNORM, launch_ln_stats(ws.ps, ws.sa, m->ln_eps, H, ws.max_rows, rows, s));
         else
             PS_TIMED(PS_FAM_LAYERNORM, launch_cls_stats(m, n_req, ws, ws.ya, ws.sa, s));   // what the head reads
         sg = w.ln2_g;

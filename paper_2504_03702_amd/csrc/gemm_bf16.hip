@@ -6,6 +6,10 @@
 //             QKV split (query and key columns to [rows][2H], value columns transposed to
 //             Vt[H][max_rows] so the attention kernel reads keys-contiguous value tiles), also as
 //             keys and values only, and as the queries of mapped rows only.
+//   A LayerNorm in front of a map is folded into it: the operand is the row before normalisation,
+//   W carries the LayerNorm's scale, and the epilogue finishes with the row's (mean, 1/std):
+//   rstd * (acc - mean * colsum[n]) + d[n].  The residual epilogues produce such operands: besides the
+//   fp32 sums they write them as bf16 and leave per-row partial sums for the statistics.
 //
 // One workgroup computes a BM x BN tile.  Per 64-deep k slice the A and W sub-tiles are brought
 // straight from global memory into LDS (global_load_lds, 16 bytes per lane, no register staging),
@@ -52,6 +56,19 @@ __device__ __forceinline__ float gelu_erf(float v) {
     q = fmaf(q, t, -1.335489713e+00f);
     q = fmaf(q, t, 3.986949891e-01f);
     return v * fmaf(xc, q, 0.5f);
+}
+
+// Sum over the 16 lanes of a DPP row (lanes 16 r .. 16 r + 15); every lane of the row gets the total.
+// The order of the additions is fixed, so the result does not change from run to run.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+    v = dpp_add<0xB1>(v);      // quad_perm [1, 0, 3, 2]
+    v = dpp_add<0x4E>(v);      // quad_perm [2, 3, 0, 1]
+    v = dpp_add<0x141>(v);     // row_half_mirror
+    return dpp_add<0x140>(v);  // row_mirror
 }
 
 template <int BM, int BN, int WM, int WN>
@@ -283,25 +300,52 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
         if ((EPI == EPI_QKV || EPI == EPI_KV) && n0 >= v_col0) {
             // Value columns go to Vt[feature][row].  One 32 x 32 accumulator tile at a time is staged as
             // [32 features][32 rows]; the 16-byte chunks of a feature's rows are XOR-swizzled with the
-            // feature index so the 128-byte-strided writes of the 32 lanes spread over the banks.
+            // feature index so the 128-byte-strided writes of the 32 lanes spread over the banks.  Read
+            // back, a lane holds 8 consecutive rows of one feature: the folded LayerNorm is finished there.
+            const int rg = lane & 3;
+            float cc[T::TN][2], dd[T::TN][2];
 #pragma unroll
-            for (int j = 0; j < T::TN; ++j) {
-                const float bj = bias[n_base + 32 * j + frow];
+            for (int j = 0; j < T::TN; ++j)
 #pragma unroll
-                for (int i = 0; i < T::TM; ++i) {
+                for (int it = 0; it < 2; ++it) {
+                    const int c = n_base + 32 * j + (lane >> 2) + 16 * it;
+                    cc[j][it] = res.colsum[c];
+                    dd[j][it] = bias[c];
+                }
+            float2 sv[2][8];                         // statistics of the lane's 8 rows, tile row i and i + 1
+            auto fetch_sv = [&](int i) {
+#pragma unroll
+                for (int r = 0; r < 8; ++r) sv[i & 1][r] = res.stats[m_base + 32 * i + 8 * rg + r];
+            };
+            fetch_sv(0);
+#pragma unroll
+            for (int i = 0; i < T::TM; ++i) {
+                if (i + 1 < T::TM) fetch_sv(i + 1);
+                float rs[8], nm[8];
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    rs[r] = sv[i & 1][r].y;
+                    nm[r] = -sv[i & 1][r].x * sv[i & 1][r].y;
+                }
+#pragma unroll
+                for (int j = 0; j < T::TN; ++j) {
 #pragma unroll
                     for (int e4 = 0; e4 < 4; ++e4) {
                         const f32x16& a = acc[i][j];
-                        const float4 v = make_float4(a[4 * e4] + bj, a[4 * e4 + 1] + bj, a[4 * e4 + 2] + bj, a[4 * e4 + 3] + bj);
-                        *(float4*)(stg + frow * 32 + 4 * ((2 * e4 + fhalf) ^ (frow & 7))) = v;
+                        *(float4*)(stg + frow * 32 + 4 * ((2 * e4 + fhalf) ^ (frow & 7))) =
+                            make_float4(a[4 * e4], a[4 * e4 + 1], a[4 * e4 + 2], a[4 * e4 + 3]);
                     }
 #pragma unroll
                     for (int it = 0; it < 2; ++it) {
-                        const int c = (lane >> 2) + 16 * it, rg = lane & 3;
+                        const int c = (lane >> 2) + 16 * it;
                         const float4 lo = *(const float4*)(stg + c * 32 + 4 * ((2 * rg) ^ (c & 7)));
                         const float4 hi = *(const float4*)(stg + c * 32 + 4 * ((2 * rg + 1) ^ (c & 7)));
-                        const uint4 o = make_uint4(cvt_pk_bf16(lo.x, lo.y), cvt_pk_bf16(lo.z, lo.w),
-                                                   cvt_pk_bf16(hi.x, hi.y), cvt_pk_bf16(hi.z, hi.w));
+                        const float a8[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                        float v[8];
+#pragma unroll
+                        for (int r = 0; r < 8; ++r) v[r] = fmaf(a8[r], rs[r], fmaf(nm[r], cc[j][it], dd[j][it]));
+                        const uint4 o = make_uint4(cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3]),
+                                                   cvt_pk_bf16(v[4], v[5]), cvt_pk_bf16(v[6], v[7]));
                         *(uint4*)(Vt + (int64_t)(n_base - v_col0 + 32 * j + c) * vt_ld + m_base + 32 * i + 8 * rg) = o;
                     }
                 }
@@ -329,6 +373,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
             const float4 rg = *(const float4*)(res.gamma + col);
             const float4 rb = *(const float4*)(res.beta + col);
             float* Cf = (float*)Cv;
+            // the sums as the next map's bf16 operand, and what this 64-column piece of the row adds to
+            // the row's sum and sum of squares (the 16 lanes of a DPP row share a row of the strip)
+            static_assert(LPR == 16 && WTN == 64, "one DPP row per row of a strip");
+            const int piece = n_base >> 6, pieces = N >> 6;
+            auto emit = [&](const float4& o, int64_t row, bool live) {
+                if (!res.x_out) return;
+                const float sm = row16_sum((o.x + o.y) + (o.z + o.w));
+                const float sq = row16_sum(fmaf(o.x, o.x, o.y * o.y) + fmaf(o.z, o.z, o.w * o.w));
+                if (live) {
+                    *(uint2*)(res.x_out + row * N + col) = make_uint2(cvt_pk_bf16(o.x, o.y), cvt_pk_bf16(o.z, o.w));
+                    if (cg == 0) res.pstats[row * pieces + piece] = make_float2(sm, sq);
+                }
+            };
             auto combine = [&](const float4& a, const float4& yp, const float2& st) {
                 float4 o;
                 o.x = a.x + bv.x + ((yp.x - st.x) * st.y * rg.x + rb.x);
@@ -364,8 +421,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
                     for (int it = 0; it < NIT; ++it) {
                         const int r = r_in + RPI * it;
                         const float4 a = *(const float4*)(stg + r * SW + 4 * cg);
-                        *(float4*)(Cf + (row0 + 8 * s + RPI * it) * N + col) =
-                            combine(a, yp[s % (D + 1)][it], st[s % (D + 1)][it]);
+                        const float4 o = combine(a, yp[s % (D + 1)][it], st[s % (D + 1)][it]);
+                        *(float4*)(Cf + (row0 + 8 * s + RPI * it) * N + col) = o;
+                        emit(o, row0 + 8 * s + RPI * it, row0 + 8 * s + RPI * it < rows);
                     }
                 }
                 continue;
@@ -384,7 +442,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
                         // GEMM row = request; its stream row is the request's first row
                         if (row >= rows || res.seq_len[row] <= 0) continue;
                         row = res.row_map[row];
-                        *(float4*)(Cf + row * N + col) = combine(a, *(const float4*)(res.y + row * N + col), res.stats[row]);
+                        const float4 o = combine(a, *(const float4*)(res.y + row * N + col), res.stats[row]);
+                        *(float4*)(Cf + row * N + col) = o;
+                        emit(o, row, true);
                     }
                 }
             continue;
@@ -396,6 +456,23 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
             const int cg = lane % LPR, r_in = lane / LPR;
             const int col = n_base + 8 * cg;
             const float4 b0 = *(const float4*)(bias + col), b1 = *(const float4*)(bias + col + 4);
+            // maps with a LayerNorm folded in: column sums, and the statistics of every row this lane
+            // will touch, requested before the first strip
+            constexpr bool FOLD = EPI == EPI_QKV || EPI == EPI_KV || EPI == EPI_Q_MAPPED || EPI == EPI_BIAS_GELU;
+            float4 c0 = make_float4(0.f, 0.f, 0.f, 0.f), c1 = c0;
+            float2 rst[FOLD ? T::TM * 4 * NIT : 1];
+            if (FOLD) {
+                c0 = *(const float4*)(res.colsum + col);
+                c1 = *(const float4*)(res.colsum + col + 4);
+#pragma unroll
+                for (int s = 0; s < T::TM * 4; ++s)
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it) {
+                        int64_t row = m_base + 8 * s + r_in + RPI * it;
+                        if (EPI == EPI_Q_MAPPED) row = (row < rows && res.seq_len[row] > 0) ? res.row_map[row] : 0;
+                        rst[s * NIT + it] = res.stats[row];
+                    }
+            }
             const int64_t ldc = (EPI == EPI_QKV || EPI == EPI_KV || EPI == EPI_Q_MAPPED) ? 2 * (int64_t)hidden
                                 : EPI == EPI_GELU_SPLIT ? 2 * (int64_t)N : (int64_t)N;
             const int c_col = col + (EPI == EPI_KV ? hidden : 0);   // key columns sit after the query columns
@@ -416,8 +493,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
                         }
                         const float4 lo = *(const float4*)(stg + r * SW + 8 * cg);
                         const float4 hi = *(const float4*)(stg + r * SW + 8 * cg + 4);
-                        float v[8] = {lo.x + b0.x, lo.y + b0.y, lo.z + b0.z, lo.w + b0.w,
-                                      hi.x + b1.x, hi.y + b1.y, hi.z + b1.z, hi.w + b1.w};
+                        float v[8];
+                        if (FOLD) {
+                            const float2 st = rst[(4 * i + e4) * NIT + it];
+                            const float nm = -st.x * st.y;
+                            v[0] = fmaf(lo.x, st.y, fmaf(nm, c0.x, b0.x)); v[1] = fmaf(lo.y, st.y, fmaf(nm, c0.y, b0.y));
+                            v[2] = fmaf(lo.z, st.y, fmaf(nm, c0.z, b0.z)); v[3] = fmaf(lo.w, st.y, fmaf(nm, c0.w, b0.w));
+                            v[4] = fmaf(hi.x, st.y, fmaf(nm, c1.x, b1.x)); v[5] = fmaf(hi.y, st.y, fmaf(nm, c1.y, b1.y));
+                            v[6] = fmaf(hi.z, st.y, fmaf(nm, c1.z, b1.z)); v[7] = fmaf(hi.w, st.y, fmaf(nm, c1.w, b1.w));
+                        } else {
+                            v[0] = lo.x + b0.x; v[1] = lo.y + b0.y; v[2] = lo.z + b0.z; v[3] = lo.w + b0.w;
+                            v[4] = hi.x + b1.x; v[5] = hi.y + b1.y; v[6] = hi.z + b1.z; v[7] = hi.w + b1.w;
+                        }
                         if (EPI == EPI_BIAS_GELU || EPI == EPI_GELU_SPLIT) {
 #pragma unroll
                             for (int e = 0; e < 8; ++e) v[e] = gelu_erf(v[e]);

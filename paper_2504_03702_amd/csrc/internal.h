@@ -25,6 +25,12 @@ struct LayerWeights {
     void *w_qkv, *w_o, *w_1, *w_2;
     void *w_od, *w_1d, *w_2d;    // bf16 models: W_o, W_1, W_2 with the contraction index repeated ([out][2 in])
     float *b_qkv, *b_o, *b_1, *b_2;
+    // bf16 models: the LayerNorm in front of the QKV and the first feed-forward map is folded into them.
+    // With x = (y - mean) * rstd * gamma + beta:  x W + b = rstd * (y (gamma W) - mean * c) + d,
+    // c[n] = sum_k gamma[k] W[k][n], d[n] = b[n] + sum_k beta[k] W[k][n].  w_qkv and w_1 hold gamma W,
+    // b_qkv holds d of the QKV map, d_1 that of W_1 (b_1 stays the plain bias: the first-row pass uses it
+    // with the plain w_1d), c_qkv and c_1 the column sums taken over the rounded gamma W.
+    float *c_qkv, *c_1, *d_1;
     float *ln1_g, *ln1_b, *ln2_g, *ln2_b;
 };
 
@@ -73,6 +79,7 @@ struct Workspace {
     // sublayers plus each row's (mean, 1/std); its LayerNorm is recomputed wherever it is needed
     float *ya, *yb;
     float2 *sa, *sb;
+    float2 *ps;                  // [rows][hidden / 64] per-row partial (sum, sum of squares) of the newest sums
     void *cls_a, *cls_g;         // per-request rows of the [CLS] refinement: [cls_rows][2H], [cls_rows][2F] bf16
     int64_t cls_rows;
     int64_t max_rows;            // rows every activation buffer holds (multiple of PS_ROW_TILE)
@@ -108,6 +115,13 @@ struct ResidualSrc {
     const float* beta;
     const int32_t* row_map;  // EPI_RESIDUAL_MAPPED: stream row of GEMM row r (the request's first row)
     const int32_t* seq_len;  //                       rows with seq_len[r] <= 0 are not stored
+    // residual epilogues, optional: the new sums also go out as bf16 (the next GEMM's operand, not
+    // normalised) and every 64-column piece of a row leaves its (sum, sum of squares) in pstats[row][N / 64]
+    bf16_t* x_out;
+    float2* pstats;
+    // epilogues of the maps a LayerNorm is folded into (EPI_QKV, EPI_KV, EPI_Q_MAPPED, EPI_BIAS_GELU):
+    // `stats` are the statistics of the operand's rows, colsum is c above and the bias argument is d
+    const float* colsum;
 };
 // C[rows, N] = A[rows, K] * W^T (+ epilogue); W is [N][K]; rows = *total_rows (device).
 // EPI_BIAS_RESIDUAL writes fp32 sums (C is float*); the other epilogues write bf16.  clk (device,
@@ -125,10 +139,9 @@ void launch_cls_stats(const ps_model* m, int32_t n_req, const Workspace& ws, con
 // first_rows_only: compute (at least) the first query row of every request and nothing beyond its
 // first 32 rows; the rest of the output buffer keeps its old contents.
 void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, bool first_rows_only, hipStream_t s);
-// x = bf16(LayerNorm(y)) and stats = (mean, 1/std) for every live row of the fp32 sums y.
-void launch_layernorm_bf16(const float* y, bf16_t* x, float2* stats, const float* gamma, const float* beta,
-                           float eps, int hidden, int64_t max_rows, const int32_t* total_rows,
-                           hipStream_t s);
+// stats[row] = (mean, 1/std) of every live row from the partial sums the residual epilogues left.
+void launch_ln_stats(const float2* pstats, float2* stats, float eps, int hidden, int64_t max_rows,
+                     const int32_t* total_rows, hipStream_t s);
 
 // Brackets the launches made during its lifetime with two events when profiling is on.
 struct ProfScope {

@@ -166,14 +166,13 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
             }
         }
         const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)H + eps);
+        // the sums in fp32 and, not normalised, as the bf16 operand of the first QKV map, which has the
+        // embedding LayerNorm folded into its weights and finishes it from the row statistics
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
             if (c < nch) {
-                const float4 g = ((const float4*)gamma)[lane + 64 * c], bt = ((const float4*)beta)[lane + 64 * c];
                 ((float4*)yrow)[lane + 64 * c] = e[c];
-                ((uint2*)out)[lane + 64 * c] =
-                    make_uint2(pack_bf16x2((e[c].x - mean) * rstd * g.x + bt.x, (e[c].y - mean) * rstd * g.y + bt.y),
-                               pack_bf16x2((e[c].z - mean) * rstd * g.z + bt.z, (e[c].w - mean) * rstd * g.w + bt.w));
+                ((uint2*)out)[lane + 64 * c] = make_uint2(pack_bf16x2(e[c].x, e[c].y), pack_bf16x2(e[c].z, e[c].w));
             }
         }
         if (lane == 0) stats_out[row] = make_float2(mean, rstd);
