@@ -110,8 +110,8 @@ Workspace plan_workspace(const ps_model_info& info, int64_t n_tokens, int32_t n_
     ws.vt = info.dtype == 1 ? take(es * rows * H + 1024) : nullptr;   // + slack: the last key tile may read past a row end
     ws.att = take(es * rows * H);
     if (info.dtype == 1) {
-        ws.ya = (float*)take(4 * rows * H);
-        ws.yb = (float*)take(4 * rows * H);
+        ws.la = (bf16_t*)take(2 * rows * H);
+        ws.lb = (bf16_t*)take(2 * rows * H);
         ws.sa = (float2*)take(8 * rows);
         ws.sb = (float2*)take(8 * rows);
         ws.ps = (float2*)take(8 * rows * (H / 64));

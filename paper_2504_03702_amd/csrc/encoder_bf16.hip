@@ -48,10 +48,10 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
            *x1 = (bf16_t*)ws.x1, *g = (bf16_t*)ws.g;
     const int32_t* rows = &ws.meta->total_rows;        // the rows that belong to requests
     const int32_t* qkv_rows = &ws.meta->qkv_rows;     // QKV projection: those plus the slack the key tiles read
-    const ResidualSrc none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    const ResidualSrc none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     const int32_t* n_req_dev = &ws.meta->n_req;
     int64_t* clk = m->profiling ? m->clk_slot : nullptr;   // clock probe of the large GEMMs
-    // the stream entering layer 0 is the embedding LayerNorm of the sums the embed kernel left in ya
+    // the stream entering layer 0 is the embedding LayerNorm of the sums the embed kernel left in (x, la)
     const float *sg = m->lne_g, *sbeta = m->lne_b;
 #define PS_TIMED(FAM, CALL) do { ProfScope p_(m, FAM, s); CALL; } while (0)
     for (int l = 0; l < f.layers; ++l) {
@@ -61,62 +61,60 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
         // all-row GEMMs and LayerNorms are skipped, attention computes the first rows only, and the
         // per-request side pass below, which every layer runs for accuracy, is all that is left.
         const bool last = l + 1 == f.layers;
-        // what the stream's new sums also leave behind unless this is the last layer: the bf16 operand of
-        // the next map (x1 for the feed-forward block, x for the next layer) and the partial statistics
-        bf16_t* x1_out = last ? nullptr : x1;
-        bf16_t* x_out = last ? nullptr : x;
+        // the sums entering the layer are (x, la), those after the attention sublayer (x1, lb); the per-row
+        // partial statistics are only needed where a map with a folded LayerNorm follows
         float2* ps = last ? nullptr : ws.ps;
-        const ResidualSrc in = {ws.ya, ws.sa, sg, sbeta, nullptr, nullptr, x1_out, ps, nullptr};
-        const ResidualSrc mid = {ws.yb, ws.sb, w.ln1_g, w.ln1_b, nullptr, nullptr, x_out, ps, nullptr};
-        const ResidualSrc mid_cls = {ws.yb, ws.sb, w.ln1_g, w.ln1_b, ws.row_start, ws.seq_len, x_out, ps, nullptr};
+        const ResidualSrc in = {x, ws.la, ws.sa, sg, sbeta, nullptr, nullptr, x1, ps, nullptr};
+        const ResidualSrc mid = {x1, ws.lb, ws.sb, w.ln1_g, w.ln1_b, nullptr, nullptr, x, ps, nullptr};
+        const ResidualSrc mid_cls = {x1, ws.lb, ws.sb, w.ln1_g, w.ln1_b, ws.row_start, ws.seq_len, x, ps, nullptr};
         // operands of the maps with a folded LayerNorm: row statistics and column sums
-        const ResidualSrc fold_qkv = {nullptr, ws.sa, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.c_qkv};
-        const ResidualSrc fold_1 = {nullptr, ws.sb, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.c_1};
+        const ResidualSrc fold_qkv = {nullptr, nullptr, ws.sa, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.c_qkv};
+        const ResidualSrc fold_1 = {nullptr, nullptr, ws.sb, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.c_1};
         if (!last) {
             PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_QKV, x, (const bf16_t*)w.w_qkv, w.b_qkv, fold_qkv, qk, vt,
                                                    ws.max_rows, 3 * H, H, H, qkv_rows, clk, s));
         } else {
             // keys and values of all rows; queries of the requests' first rows only, by a side GEMM on
             // those rows gathered into the (not yet used) first-row buffer
-            const ResidualSrc fold_kv = {nullptr, ws.sa, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.c_qkv + H};
+            const ResidualSrc fold_kv = {nullptr, nullptr, ws.sa, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, w.c_qkv + H};
             PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_KV, x, (const bf16_t*)w.w_qkv + (size_t)H * H, w.b_qkv + H, fold_kv,
                                                    qk, vt, ws.max_rows, 2 * H, H, H, qkv_rows, clk, s));
-            const ResidualSrc first_rows = {nullptr, ws.sa, nullptr, nullptr, ws.row_start, ws.seq_len, nullptr, nullptr, w.c_qkv};
+            const ResidualSrc first_rows = {nullptr, nullptr, ws.sa, nullptr, nullptr, ws.row_start, ws.seq_len, nullptr, nullptr, w.c_qkv};
             PS_TIMED(PS_FAM_REFINE, launch_cls_rows(m, n_req, ws, x, (bf16_t*)ws.cls_a, s));
             PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_Q_MAPPED, (const bf16_t*)ws.cls_a, (const bf16_t*)w.w_qkv, w.b_qkv,
                                                      first_rows, qk, nullptr, ws.cls_rows, H, H, H, n_req_dev, nullptr, s));
         }
         PS_TIMED(PS_FAM_ATTENTION, launch_attention_bf16(m, n_req, ws, last, s));
         if (!last)
-            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, att, (const bf16_t*)w.w_o, w.b_o, in, ws.yb,
+            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, att, (const bf16_t*)w.w_o, w.b_o, in, ws.lb,
                                                    nullptr, ws.max_rows, H, H, H, rows, clk, s));
         // output projection again for each request's first row from the hi | lo pairs the attention
         // kernel left in cls_a (see the feed-forward refinement below)
-        const ResidualSrc in_cls = {ws.ya, ws.sa, sg, sbeta, ws.row_start, ws.seq_len, x1_out, ps, nullptr};
+        const ResidualSrc in_cls = {x, ws.la, ws.sa, sg, sbeta, ws.row_start, ws.seq_len, x1, ps, nullptr};
         PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_RESIDUAL_MAPPED, (const bf16_t*)ws.cls_a, (const bf16_t*)w.w_od,
-                                                 w.b_o, in_cls, ws.yb, nullptr, ws.cls_rows, H, 2 * H, H, n_req_dev, nullptr, s));
+                                                 w.b_o, in_cls, ws.lb, nullptr, ws.cls_rows, H, 2 * H, H, n_req_dev, nullptr, s));
         if (!last) {
             PS_TIMED(PS_FAM_LAYERNORM, launch_ln_stats(ws.ps, ws.sb, m->ln_eps, H, ws.max_rows, rows, s));
             PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_GELU, x1, (const bf16_t*)w.w_1, w.d_1, fold_1, g, nullptr,
                                                    ws.max_rows, F, H, H, rows, clk, s));
-            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, g, (const bf16_t*)w.w_2, w.b_2, mid, ws.ya,
+            PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_RESIDUAL, g, (const bf16_t*)w.w_2, w.b_2, mid, ws.la,
                                                    nullptr, ws.max_rows, H, F, H, rows, clk, s));
         } else {
-            PS_TIMED(PS_FAM_LAYERNORM, launch_cls_stats(m, n_req, ws, ws.yb, ws.sb, s));
+            PS_TIMED(PS_FAM_LAYERNORM, launch_cls_stats(m, n_req, ws, x1, ws.lb, ws.sb, s));
         }
         // The feed-forward block again for each request's first row, the one the head reads, with its
         // input and its GELU output carried as two bf16 values per element (contraction length doubled,
         // weights repeated): bf16 rounding of these two tensors is the dominant error of the prediction
         // and acts row by row, so the pass removes it where it matters at < 1 % of the block's cost.
-        PS_TIMED(PS_FAM_REFINE, launch_cls_gather(m, n_req, ws, ws.yb, ws.sb, w.ln1_g, w.ln1_b, s));
+        PS_TIMED(PS_FAM_REFINE, launch_cls_gather(m, n_req, ws, x1, ws.lb, ws.sb, w.ln1_g, w.ln1_b, s));
         PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_GELU_SPLIT, (const bf16_t*)ws.cls_a, (const bf16_t*)w.w_1d, w.b_1,
                                                  none, ws.cls_g, nullptr, ws.cls_rows, F, 2 * H, H, n_req_dev, nullptr, s));
         PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_RESIDUAL_MAPPED, (const bf16_t*)ws.cls_g, (const bf16_t*)w.w_2d,
-                                                 w.b_2, mid_cls, ws.ya, nullptr, ws.cls_rows, H, 2 * F, H, n_req_dev, nullptr, s));
+                                                 w.b_2, mid_cls, ws.la, nullptr, ws.cls_rows, H, 2 * F, H, n_req_dev, nullptr, s));
         if (!last)
             PS_TIMED(PS_FAM_LAYERNORM, launch_ln_stats(ws.ps, ws.sa, m->ln_eps, H, ws.max_rows, rows, s));
         else
-            PS_TIMED(PS_FAM_LAYERNORM, launch_cls_stats(m, n_req, ws, ws.ya, ws.sa, s));   // what the head reads
+            PS_TIMED(PS_FAM_LAYERNORM, launch_cls_stats(m, n_req, ws, x, ws.la, ws.sa, s));   // what the head reads
         sg = w.ln2_g;
         sbeta = w.ln2_b;
     }

@@ -2,14 +2,15 @@
 //
 //   C[m, n] = sum_k A[m, k] * W[n, k]   (A: activations [rows][K], W: weights [N][K], both bf16,
 //                                        contraction index contiguous; fp32 accumulation)
-//   epilogue: + bias[n], then one of: store | erf-GELU, store | + residual stream, store fp32 |
+//   epilogue: + bias[n], then one of: store | erf-GELU, store | + residual stream, store as hi + lo |
 //             QKV split (query and key columns to [rows][2H], value columns transposed to
 //             Vt[H][max_rows] so the attention kernel reads keys-contiguous value tiles), also as
 //             keys and values only, and as the queries of mapped rows only.
 //   A LayerNorm in front of a map is folded into it: the operand is the row before normalisation,
 //   W carries the LayerNorm's scale, and the epilogue finishes with the row's (mean, 1/std):
-//   rstd * (acc - mean * colsum[n]) + d[n].  The residual epilogues produce such operands: besides the
-//   fp32 sums they write them as bf16 and leave per-row partial sums for the statistics.
+//   rstd * (acc - mean * colsum[n]) + d[n].  The residual epilogues produce such operands: they write
+//   the new sums as two bf16 values hi + lo (hi is the operand) and leave per-row partial sums for the
+//   statistics.
 //
 // One workgroup computes a BM x BN tile.  Per 64-deep k slice the A and W sub-tiles are brought
 // straight from global memory into LDS (global_load_lds, 16 bytes per lane, no register staging),
@@ -58,17 +59,16 @@ __device__ __forceinline__ float gelu_erf(float v) {
     return v * fmaf(xc, q, 0.5f);
 }
 
-// Sum over the 16 lanes of a DPP row (lanes 16 r .. 16 r + 15); every lane of the row gets the total.
+// Sum over 8 consecutive lanes (lanes 8 r .. 8 r + 7) with DPP moves; every one of them gets the total.
 // The order of the additions is fixed, so the result does not change from run to run.
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float v) {
     return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
-__device__ __forceinline__ float row16_sum(float v) {
+__device__ __forceinline__ float row8_sum(float v) {
     v = dpp_add<0xB1>(v);      // quad_perm [1, 0, 3, 2]
     v = dpp_add<0x4E>(v);      // quad_perm [2, 3, 0, 1]
-    v = dpp_add<0x141>(v);     // row_half_mirror
-    return dpp_add<0x140>(v);  // row_mirror
+    return dpp_add<0x141>(v);  // row_half_mirror: lane i of each group of 8 takes lane 7 - i
 }
 
 template <int BM, int BN, int WM, int WN>
@@ -364,35 +364,61 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
         };
 
         if (EPI == EPI_BIAS_RESIDUAL || EPI == EPI_RESIDUAL_MAPPED) {
-            // fp32 sums out: v = acc + bias + LayerNorm(y_prev) recomputed from the row statistics, so
-            // the residual stream is never rounded to bf16.  A lane handles 4 consecutive columns.
-            constexpr int LPR = WTN / 4, RPI = 64 / LPR, NIT = 8 / RPI, NS = 4 * T::TM;
+            // New sums of the residual stream: v = acc + bias + LayerNorm(y_prev) recomputed from the
+            // previous sums (kept as two bf16, hi + lo) and the row statistics, so the stream is never
+            // rounded to 8 bits.  v goes out as hi + lo again: hi is what the next map reads.  A lane
+            // handles 8 consecutive columns (16-byte accesses), 8 lanes a row of the strip.
+            constexpr int LPR = WTN / 8, RPI = 64 / LPR, NIT = 8 / RPI, NS = 4 * T::TM;
+            static_assert(LPR == 8 && NIT == 1, "8 lanes per 64-column row piece");
             const int cg = lane % LPR, r_in = lane / LPR;
-            const int col = n_base + 4 * cg;
-            const float4 bv = *(const float4*)(bias + col);
-            const float4 rg = *(const float4*)(res.gamma + col);
-            const float4 rb = *(const float4*)(res.beta + col);
-            float* Cf = (float*)Cv;
-            // the sums as the next map's bf16 operand, and what this 64-column piece of the row adds to
-            // the row's sum and sum of squares (the 16 lanes of a DPP row share a row of the strip)
-            static_assert(LPR == 16 && WTN == 64, "one DPP row per row of a strip");
+            const int col = n_base + 8 * cg;
+            float bv[8], rg[8], rb[8];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float4 b4 = *(const float4*)(bias + col + 4 * h);
+                const float4 g4 = *(const float4*)(res.gamma + col + 4 * h);
+                const float4 e4 = *(const float4*)(res.beta + col + 4 * h);
+                bv[4 * h] = b4.x; bv[4 * h + 1] = b4.y; bv[4 * h + 2] = b4.z; bv[4 * h + 3] = b4.w;
+                rg[4 * h] = g4.x; rg[4 * h + 1] = g4.y; rg[4 * h + 2] = g4.z; rg[4 * h + 3] = g4.w;
+                rb[4 * h] = e4.x; rb[4 * h + 1] = e4.y; rb[4 * h + 2] = e4.z; rb[4 * h + 3] = e4.w;
+            }
+            bf16_t* Cl = (bf16_t*)Cv;
             const int piece = n_base >> 6, pieces = N >> 6;
-            auto emit = [&](const float4& o, int64_t row, bool live) {
-                if (!res.x_out) return;
-                const float sm = row16_sum((o.x + o.y) + (o.z + o.w));
-                const float sq = row16_sum(fmaf(o.x, o.x, o.y * o.y) + fmaf(o.z, o.z, o.w * o.w));
-                if (live) {
-                    *(uint2*)(res.x_out + row * N + col) = make_uint2(cvt_pk_bf16(o.x, o.y), cvt_pk_bf16(o.z, o.w));
-                    if (cg == 0) res.pstats[row * pieces + piece] = make_float2(sm, sq);
+            // one row of a strip: combine, store hi and lo, and (where asked for) leave the 64-column
+            // piece's sum and sum of squares, added up over the row's 8 lanes
+            auto finish_row = [&](int r, const uint4& h, const uint4& l, const float2& st, int64_t row, bool live) {
+                const float4 a0 = *(const float4*)(stg + r * SW + 8 * cg);
+                const float4 a1 = *(const float4*)(stg + r * SW + 8 * cg + 4);
+                const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+                const uint32_t hw[4] = {h.x, h.y, h.z, h.w}, lw[4] = {l.x, l.y, l.z, l.w};
+                float o[8];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float y0 = __uint_as_float(hw[t] << 16) + __uint_as_float(lw[t] << 16);
+                    const float y1 = __uint_as_float(hw[t] & 0xffff0000u) + __uint_as_float(lw[t] & 0xffff0000u);
+                    o[2 * t] = a[2 * t] + bv[2 * t] + ((y0 - st.x) * st.y * rg[2 * t] + rb[2 * t]);
+                    o[2 * t + 1] = a[2 * t + 1] + bv[2 * t + 1] + ((y1 - st.x) * st.y * rg[2 * t + 1] + rb[2 * t + 1]);
                 }
-            };
-            auto combine = [&](const float4& a, const float4& yp, const float2& st) {
-                float4 o;
-                o.x = a.x + bv.x + ((yp.x - st.x) * st.y * rg.x + rb.x);
-                o.y = a.y + bv.y + ((yp.y - st.x) * st.y * rg.y + rb.y);
-                o.z = a.z + bv.z + ((yp.z - st.x) * st.y * rg.z + rb.z);
-                o.w = a.w + bv.w + ((yp.w - st.x) * st.y * rg.w + rb.w);
-                return o;
+                float sm = 0.f, sq = 0.f;
+                if (res.pstats) {
+                    sm = ((o[0] + o[1]) + (o[2] + o[3])) + ((o[4] + o[5]) + (o[6] + o[7]));
+                    sq = (fmaf(o[0], o[0], o[1] * o[1]) + fmaf(o[2], o[2], o[3] * o[3])) +
+                         (fmaf(o[4], o[4], o[5] * o[5]) + fmaf(o[6], o[6], o[7] * o[7]));
+                    sm = row8_sum(sm);
+                    sq = row8_sum(sq);
+                }
+                if (live) {
+                    uint32_t ho[4], lo[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        ho[t] = cvt_pk_bf16(o[2 * t], o[2 * t + 1]);
+                        lo[t] = cvt_pk_bf16(o[2 * t] - __uint_as_float(ho[t] << 16),
+                                            o[2 * t + 1] - __uint_as_float(ho[t] & 0xffff0000u));
+                    }
+                    *(uint4*)(res.x_out + row * N + col) = make_uint4(ho[0], ho[1], ho[2], ho[3]);
+                    *(uint4*)(Cl + row * N + col) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                    if (res.pstats && cg == 0) res.pstats[row * pieces + piece] = make_float2(sm, sq);
+                }
             };
             if (EPI == EPI_BIAS_RESIDUAL) {
                 // The previous sums and statistics of strip s + D are requested before strip s is worked
@@ -400,16 +426,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
                 // 8 s .. 8 s + 7 of the wavefront's tile.
                 constexpr int D = 3;
                 const int64_t row0 = m_base + r_in;
-                const float* yb = res.y + row0 * N + col;
+                const bf16_t* yh = res.y_hi + row0 * N + col;
+                const bf16_t* yl = res.y_lo + row0 * N + col;
                 const float2* sb = res.stats + row0;
-                float4 yp[D + 1][NIT];
-                float2 st[D + 1][NIT];
+                uint4 ph[D + 1], pl[D + 1];
+                float2 st[D + 1];
                 auto fetch = [&](int s) {
-#pragma unroll
-                    for (int it = 0; it < NIT; ++it) {
-                        yp[s % (D + 1)][it] = *(const float4*)(yb + (int64_t)(8 * s + RPI * it) * N);
-                        st[s % (D + 1)][it] = sb[8 * s + RPI * it];
-                    }
+                    ph[s % (D + 1)] = *(const uint4*)(yh + (int64_t)(8 * s) * N);
+                    pl[s % (D + 1)] = *(const uint4*)(yl + (int64_t)(8 * s) * N);
+                    st[s % (D + 1)] = sb[8 * s];
                 };
 #pragma unroll
                 for (int s = 0; s < D; ++s) fetch(s);
@@ -417,14 +442,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
                 for (int s = 0; s < NS; ++s) {
                     if (s + D < NS) fetch(s + D);
                     stage_strip(s / 4, s % 4);
-#pragma unroll
-                    for (int it = 0; it < NIT; ++it) {
-                        const int r = r_in + RPI * it;
-                        const float4 a = *(const float4*)(stg + r * SW + 4 * cg);
-                        const float4 o = combine(a, yp[s % (D + 1)][it], st[s % (D + 1)][it]);
-                        *(float4*)(Cf + (row0 + 8 * s + RPI * it) * N + col) = o;
-                        emit(o, row0 + 8 * s + RPI * it, row0 + 8 * s + RPI * it < rows);
-                    }
+                    const int64_t row = row0 + 8 * s;
+                    finish_row(r_in, ph[s % (D + 1)], pl[s % (D + 1)], st[s % (D + 1)], row, row < rows);
                 }
                 continue;
             }
@@ -434,18 +453,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
 #pragma unroll
                 for (int e4 = 0; e4 < 4; ++e4) {
                     stage_strip(i, e4);
-#pragma unroll
-                    for (int it = 0; it < NIT; ++it) {
-                        const int r = r_in + RPI * it;
-                        int64_t row = m_base + 32 * i + 8 * e4 + r;
-                        const float4 a = *(const float4*)(stg + r * SW + 4 * cg);
-                        // GEMM row = request; its stream row is the request's first row
-                        if (row >= rows || res.seq_len[row] <= 0) continue;
-                        row = res.row_map[row];
-                        const float4 o = combine(a, *(const float4*)(res.y + row * N + col), res.stats[row]);
-                        *(float4*)(Cf + row * N + col) = o;
-                        emit(o, row, true);
-                    }
+                    int64_t row = m_base + 32 * i + 8 * e4 + r_in;
+                    // GEMM row = request; its stream row is the request's first row
+                    if (row >= rows || res.seq_len[row] <= 0) continue;
+                    row = res.row_map[row];
+                    finish_row(r_in, *(const uint4*)(res.y_hi + row * N + col), *(const uint4*)(res.y_lo + row * N + col),
+                               res.stats[row], row, true);
                 }
             continue;
         }

@@ -75,9 +75,11 @@ struct Workspace {
     int32_t *qtile_start;        // [B+1] first attention query tile of request r
     int32_t *bad_req;            // [B]   set when a request's text holds an invalid token id
     void *x, *qkv, *vt, *att, *y, *x1, *g;
-    // bf16 path: the residual stream is kept in fp32 as the pre-LayerNorm sums of the last two
-    // sublayers plus each row's (mean, 1/std); its LayerNorm is recomputed wherever it is needed
-    float *ya, *yb;
+    // bf16 path: the residual stream is kept as the pre-LayerNorm sums of the last two sublayers,
+    // each sum as two bf16 values hi + lo (16 significant bits), plus each row's (mean, 1/std); its
+    // LayerNorm is recomputed wherever it is needed.  The hi parts are x (sums entering a layer) and x1
+    // (sums after the attention sublayer): exactly the operands of the maps the LayerNorms are folded into.
+    bf16_t *la, *lb;             // lo parts belonging to x and x1
     float2 *sa, *sb;
     float2 *ps;                  // [rows][hidden / 64] per-row partial (sum, sum of squares) of the newest sums
     void *cls_a, *cls_g;         // per-request rows of the [CLS] refinement: [cls_rows][2H], [cls_rows][2F] bf16
@@ -109,14 +111,16 @@ enum GemmEpilogue {
 };
 // The residual stream entering a sublayer: LayerNorm(y) with the row statistics already known.
 struct ResidualSrc {
-    const float* y;          // [rows][hidden] fp32 pre-LayerNorm sums
+    const bf16_t* y_hi;      // [rows][hidden] pre-LayerNorm sums, value = hi + lo
+    const bf16_t* y_lo;
     const float2* stats;     // [rows] (mean, 1 / sqrt(var + eps))
     const float* gamma;
     const float* beta;
     const int32_t* row_map;  // EPI_RESIDUAL_MAPPED: stream row of GEMM row r (the request's first row)
     const int32_t* seq_len;  //                       rows with seq_len[r] <= 0 are not stored
-    // residual epilogues, optional: the new sums also go out as bf16 (the next GEMM's operand, not
-    // normalised) and every 64-column piece of a row leaves its (sum, sum of squares) in pstats[row][N / 64]
+    // residual epilogues: the hi parts of the new sums (the lo parts go to the C argument); hi is also
+    // the next map's operand.  Optional: every 64-column piece of a row leaves its (sum, sum of squares)
+    // in pstats[row][N / 64]
     bf16_t* x_out;
     float2* pstats;
     // epilogues of the maps a LayerNorm is folded into (EPI_QKV, EPI_KV, EPI_Q_MAPPED, EPI_BIAS_GELU):
@@ -124,18 +128,18 @@ struct ResidualSrc {
     const float* colsum;
 };
 // C[rows, N] = A[rows, K] * W^T (+ epilogue); W is [N][K]; rows = *total_rows (device).
-// EPI_BIAS_RESIDUAL writes fp32 sums (C is float*); the other epilogues write bf16.  clk (device,
+// The residual epilogues write the new sums as hi (residual.x_out) + lo (C) bf16 pairs; all epilogues write bf16.  clk (device,
 // may be null): workgroup 0 leaves {core clock cycles, constant-rate timer ticks} of its run there.
 void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias,
                       ResidualSrc res, void* C, bf16_t* vt, int64_t max_rows, int N, int K,
                       int hidden, const int32_t* total_rows, int64_t* clk, hipStream_t s);
-void launch_cls_gather(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, const float2* stats,
-                       const float* gamma, const float* beta, hipStream_t s);
+void launch_cls_gather(const ps_model* m, int32_t n_req, const Workspace& ws, const bf16_t* y_hi, const bf16_t* y_lo,
+                       const float2* stats, const float* gamma, const float* beta, hipStream_t s);
 // out[r][0:hidden] = x[first row of request r] for every request (zeros for faulty ones and padding rows).
 void launch_cls_rows(const ps_model* m, int32_t n_req, const Workspace& ws, const bf16_t* x, bf16_t* out, hipStream_t s);
-// stats[first row of request r] = LayerNorm statistics of that row of y, for every request.
-void launch_cls_stats(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, float2* stats,
-                      hipStream_t s);
+// stats[first row of request r] = LayerNorm statistics of that row of the sums hi + lo, for every request.
+void launch_cls_stats(const ps_model* m, int32_t n_req, const Workspace& ws, const bf16_t* y_hi, const bf16_t* y_lo,
+                      float2* stats, hipStream_t s);
 // first_rows_only: compute (at least) the first query row of every request and nothing beyond its
 // first 32 rows; the rest of the output buffer keeps its old contents.
 void launch_attention_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, bool first_rows_only, hipStream_t s);

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
                                                     const int32_t* __restrict__ seq_len,
                                                     const int32_t* __restrict__ row_start,
                                                     int32_t* bad_req, T* __restrict__ x,
-                                                    float* __restrict__ y_out, float2* __restrict__ stats_out,
+                                                    bf16_t* __restrict__ lo_out, float2* __restrict__ stats_out,
                                                     ps_status* st) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
     const int64_t live = ((int64_t)total + PS_KEY_SLACK + PS_ROW_TILE - 1) / PS_ROW_TILE * PS_ROW_TILE;
     if (row >= live) return;
     T* out = x + row * H;
-    float* yrow = y_out ? y_out + row * H : nullptr;     // bf16 path: the fp32 sums and row statistics
+    bf16_t* yrow = lo_out ? lo_out + row * H : nullptr;  // bf16 path: lo parts of the sums, and row statistics
     int r = -1, p = 0;
     if (row < total) {
         int lo = 0, hi = n_req - 1;          // largest r with row_start[r] <= row
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
     if (r < 0 || p >= S) {
         for (int i = lane; i < H; i += 64) {
             store_elem<T>(out, i, 0.f);
-            if (yrow) yrow[i] = 0.f;
+            if (yrow) yrow[i] = 0;
         }
         if (yrow && lane == 0) stats_out[row] = make_float2(0.f, 0.f);
         return;
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
             }
             for (int i = lane; i < H; i += 64) {
                 store_elem<T>(out, i, 0.f);
-                if (yrow) yrow[i] = 0.f;
+                if (yrow) yrow[i] = 0;
             }
             if (yrow && lane == 0) stats_out[row] = make_float2(0.f, 0.f);
             return;
@@ -166,13 +166,16 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
             }
         }
         const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)H + eps);
-        // the sums in fp32 and, not normalised, as the bf16 operand of the first QKV map, which has the
+        // the sums as hi + lo; hi, not normalised, is the operand of the first QKV map, which has the
         // embedding LayerNorm folded into its weights and finishes it from the row statistics
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
             if (c < nch) {
-                ((float4*)yrow)[lane + 64 * c] = e[c];
-                ((uint2*)out)[lane + 64 * c] = make_uint2(pack_bf16x2(e[c].x, e[c].y), pack_bf16x2(e[c].z, e[c].w));
+                const uint2 hi = make_uint2(pack_bf16x2(e[c].x, e[c].y), pack_bf16x2(e[c].z, e[c].w));
+                ((uint2*)out)[lane + 64 * c] = hi;
+                ((uint2*)yrow)[lane + 64 * c] =
+                    make_uint2(pack_bf16x2(e[c].x - __uint_as_float(hi.x << 16), e[c].y - __uint_as_float(hi.x & 0xffff0000u)),
+                               pack_bf16x2(e[c].z - __uint_as_float(hi.y << 16), e[c].w - __uint_as_float(hi.y & 0xffff0000u)));
             }
         }
         if (lane == 0) stats_out[row] = make_float2(mean, rstd);
@@ -190,7 +193,6 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
     for (int i = lane; i < H; i += 64) {
         const float e = load_elem<T>(src, i) + load_elem<T>(pos, i);
         store_elem<T>(out, i, (e - mean) * rstd * gamma[i] + beta[i]);
-        if (yrow) yrow[i] = e;
     }
     if (yrow && lane == 0) stats_out[row] = make_float2(mean, rstd);
 }
@@ -206,7 +208,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, const int32_t* __restrict__ seq_len,
                                                    const int32_t* __restrict__ row_start,
                                                    const int32_t* __restrict__ bad_req,
-                                                   const float* __restrict__ y, const float2* __restrict__ stats,
+                                                   const bf16_t* __restrict__ y_lo, const float2* __restrict__ stats,
                                                    const float* __restrict__ ln_g, const float* __restrict__ ln_b,
                                                    int H, int Hh,
                                                    const float* __restrict__ w_h1t, const float* __restrict__ b_h1,
@@ -224,9 +226,13 @@ __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, cons
         return;
     }
     const int64_t crow = row_start[r];
-    if (y) {
+    if (y_lo) {
+        // bf16 models: x holds the hi parts of the last sums
         const float2 st2 = stats[crow];
-        for (int i = threadIdx.x; i < H; i += 256) s_c[i] = (y[crow * H + i] - st2.x) * st2.y * ln_g[i] + ln_b[i];
+        const bf16_t* hi = (const bf16_t*)x + crow * H;
+        const bf16_t* lo = y_lo + crow * H;
+        for (int i = threadIdx.x; i < H; i += 256)
+            s_c[i] = ((bf16_to_f32(hi[i]) + bf16_to_f32(lo[i])) - st2.x) * st2.y * ln_g[i] + ln_b[i];
     } else {
         const T* c = x + crow * H;
         for (int i = threadIdx.x; i < H; i += 256) s_c[i] = load_elem<T>(c, i);
@@ -258,7 +264,8 @@ __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, cons
 // Gather for the [CLS] refinement: row r of the side matrix is the fp32 LayerNorm output of request
 // r's first row, split into two bf16 values per element (x ~ hi + lo, |x - hi - lo| <= 2^-17 |x|),
 // hi in columns [0, H), lo in [H, 2H).  Rows of faulty requests and padding rows are zero.
-__global__ __launch_bounds__(256) void cls_gather_kernel(const float* __restrict__ y, const float2* __restrict__ stats,
+__global__ __launch_bounds__(256) void cls_gather_kernel(const bf16_t* __restrict__ y_hi, const bf16_t* __restrict__ y_lo,
+                                                         const float2* __restrict__ stats,
                                                          const float* __restrict__ gamma, const float* __restrict__ beta,
                                                          int H, int n_req, const int32_t* __restrict__ seq_len,
                                                          const int32_t* __restrict__ row_start, bf16_t* __restrict__ out) {
@@ -272,7 +279,7 @@ __global__ __launch_bounds__(256) void cls_gather_kernel(const float* __restrict
     const int64_t row = row_start[r];
     const float2 st = stats[row];
     for (int i = lane; i < H; i += 64) {
-        const float x = (y[row * H + i] - st.x) * st.y * gamma[i] + beta[i];
+        const float x = ((bf16_to_f32(y_hi[row * H + i]) + bf16_to_f32(y_lo[row * H + i])) - st.x) * st.y * gamma[i] + beta[i];
         const bf16_t hi = f32_to_bf16(x);
         o[i] = hi;
         o[H + i] = f32_to_bf16(x - bf16_to_f32(hi));
@@ -282,20 +289,21 @@ __global__ __launch_bounds__(256) void cls_gather_kernel(const float* __restrict
 // LayerNorm statistics (mean, 1 / std; biased variance) of each request's first row of the fp32 sums y:
 // one wavefront per request.  Used where only those rows go on (the last layer), in place of the
 // LayerNorm over all rows.
-__global__ __launch_bounds__(256) void cls_stats_kernel(const float* __restrict__ y, float2* __restrict__ stats, float eps,
+__global__ __launch_bounds__(256) void cls_stats_kernel(const bf16_t* __restrict__ y_hi, const bf16_t* __restrict__ y_lo,
+                                                        float2* __restrict__ stats, float eps,
                                                         int H, int n_req, const int32_t* __restrict__ seq_len,
                                                         const int32_t* __restrict__ row_start) {
     const int lane = threadIdx.x & 63;
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= n_req || seq_len[r] <= 0) return;
     const int64_t row = row_start[r];
-    const float* yr = y + row * H;
+    const bf16_t *yh = y_hi + row * H, *yl = y_lo + row * H;
     float sum = 0.f;
-    for (int i = lane; i < H; i += 64) sum += yr[i];
+    for (int i = lane; i < H; i += 64) sum += bf16_to_f32(yh[i]) + bf16_to_f32(yl[i]);
     const float mean = wave_sum(sum) / (float)H;
     float sq = 0.f;
     for (int i = lane; i < H; i += 64) {
-        const float d = yr[i] - mean;
+        const float d = (bf16_to_f32(yh[i]) + bf16_to_f32(yl[i])) - mean;
         sq = fmaf(d, d, sq);
     }
     const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)H + eps);
@@ -322,15 +330,15 @@ void launch_cls_rows(const ps_model* m, int32_t n_req, const Workspace& ws, cons
                        ws.seq_len, ws.row_start, out);
 }
 
-void launch_cls_stats(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, float2* stats,
-                      hipStream_t s) {
-    hipLaunchKernelGGL(cls_stats_kernel, dim3((unsigned)(ws.cls_rows / 4)), dim3(256), 0, s, y, stats, m->ln_eps,
+void launch_cls_stats(const ps_model* m, int32_t n_req, const Workspace& ws, const bf16_t* y_hi, const bf16_t* y_lo,
+                      float2* stats, hipStream_t s) {
+    hipLaunchKernelGGL(cls_stats_kernel, dim3((unsigned)(ws.cls_rows / 4)), dim3(256), 0, s, y_hi, y_lo, stats, m->ln_eps,
                        m->info.hidden, n_req, ws.seq_len, ws.row_start);
 }
 
-void launch_cls_gather(const ps_model* m, int32_t n_req, const Workspace& ws, const float* y, const float2* stats,
-                       const float* gamma, const float* beta, hipStream_t s) {
-    hipLaunchKernelGGL(cls_gather_kernel, dim3((unsigned)(ws.cls_rows / 4)), dim3(256), 0, s, y, stats, gamma, beta,
+void launch_cls_gather(const ps_model* m, int32_t n_req, const Workspace& ws, const bf16_t* y_hi, const bf16_t* y_lo,
+                       const float2* stats, const float* gamma, const float* beta, hipStream_t s) {
+    hipLaunchKernelGGL(cls_gather_kernel, dim3((unsigned)(ws.cls_rows / 4)), dim3(256), 0, s, y_hi, y_lo, stats, gamma, beta,
                        m->info.hidden, n_req, ws.seq_len, ws.row_start, (bf16_t*)ws.cls_a);
 }
 
@@ -348,12 +356,12 @@ void launch_embed(const ps_model* m, const int32_t* token_ids, const int32_t* of
         hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, token_ids, offsets, n_req,
                            (const bf16_t*)m->e_tok, (const bf16_t*)m->e_pos, (const bf16_t*)m->e_soft,
                            m->lne_g, m->lne_b, m->ln_eps, f.hidden, f.vocab, f.n_soft, ws.meta, ws.seq_len,
-                           ws.row_start, ws.bad_req, (bf16_t*)ws.x, ws.ya, ws.sa, st);
+                           ws.row_start, ws.bad_req, (bf16_t*)ws.x, ws.la, ws.sa, st);
     else
         hipLaunchKernelGGL(embed_kernel<float>, dim3(blocks), dim3(256), 0, s, token_ids, offsets, n_req,
                            (const float*)m->e_tok, (const float*)m->e_pos, (const float*)m->e_soft,
                            m->lne_g, m->lne_b, m->ln_eps, f.hidden, f.vocab, f.n_soft, ws.meta, ws.seq_len,
-                           ws.row_start, ws.bad_req, (float*)ws.x, (float*)nullptr, (float2*)nullptr, st);
+                           ws.row_start, ws.bad_req, (float*)ws.x, (bf16_t*)nullptr, (float2*)nullptr, st);
 }
 
 void launch_head(const ps_model* m, int32_t n_req, const Workspace& ws, float* pred_f, int32_t* pred_tokens,
@@ -362,12 +370,12 @@ void launch_head(const ps_model* m, int32_t n_req, const Workspace& ws, float* p
     const size_t lds = sizeof(float) * (size_t)(f.hidden + 4);
     if (f.dtype == 1)
         hipLaunchKernelGGL(head_kernel<bf16_t>, dim3(n_req), dim3(256), lds, s, (const bf16_t*)ws.x,
-                           ws.seq_len, ws.row_start, ws.bad_req, (const float*)ws.ya, (const float2*)ws.sa,
+                           ws.seq_len, ws.row_start, ws.bad_req, (const bf16_t*)ws.la, (const float2*)ws.sa,
                            (const float*)m->layers.back().ln2_g, (const float*)m->layers.back().ln2_b, f.hidden, f.head_hidden, m->w_h1t, m->b_h1, m->w_h2,
                            m->b_h2, f.d_max, pred_f, pred_tokens, st);
     else
         hipLaunchKernelGGL(head_kernel<float>, dim3(n_req), dim3(256), lds, s, (const float*)ws.x,
-                           ws.seq_len, ws.row_start, ws.bad_req, (const float*)nullptr, (const float2*)nullptr,
+                           ws.seq_len, ws.row_start, ws.bad_req, (const bf16_t*)nullptr, (const float2*)nullptr,
                            (const float*)nullptr, (const float*)nullptr, f.hidden, f.head_hidden, m->w_h1t, m->b_h1, m->w_h2,
                            m->b_h2, f.d_max, pred_f, pred_tokens, st);
 }
