@@ -1,6 +1,6 @@
 // bf16 encoder path: the per-layer sequence of MFMA GEMMs and attention launches.  There is no
-// LayerNorm kernel: a residual epilogue writes the new sums in fp32 (the residual stream), as bf16
-// (the next map's operand) and as per-row partial sums; a small kernel turns those into (mean, 1/std),
+// LayerNorm kernel: a residual epilogue writes the new sums of the residual stream as two bf16 values
+// hi + lo (hi is the next map's operand) and leaves per-row partial sums; a small kernel turns those into (mean, 1/std),
 // and the next map, which carries the LayerNorm's scale and shift in its weights, finishes the
 // normalisation in its own epilogue.
 #include "device_util.h"

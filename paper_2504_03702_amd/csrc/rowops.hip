@@ -286,7 +286,7 @@ __global__ __launch_bounds__(256) void cls_gather_kernel(const bf16_t* __restric
     }
 }
 
-// LayerNorm statistics (mean, 1 / std; biased variance) of each request's first row of the fp32 sums y:
+// LayerNorm statistics (mean, 1 / std; biased variance) of each request's first row of the sums hi + lo:
 // one wavefront per request.  Used where only those rows go on (the last layer), in place of the
 // LayerNorm over all rows.
 __global__ __launch_bounds__(256) void cls_stats_kernel(const bf16_t* __restrict__ y_hi, const bf16_t* __restrict__ y_lo,
