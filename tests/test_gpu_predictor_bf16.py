@@ -63,6 +63,19 @@ def test_single_layer_model(tmp_models):
     check(model, ref, wl.pack_prompts(lengths, ids))
 
 
+def test_widest_model(tmp_models):
+    """hidden = 2048, the widest the bf16 kernels accept: 32 heads, 8 tile columns in the hidden-wide maps,
+    32 partial row sums per row; LayerNorm scale and shift well away from 1 and 0 (they are folded into
+    the weights of the following map), a mean offset in the residual stream through the biases."""
+    cfg = wl.ModelConfig(layers=3, hidden=2048, heads=32, ffn=512, vocab=500, max_pos=300, head_hidden=64,
+                         dtype=wl.DTYPE_BF16)
+    model, ref = make(tmp_models, "wide_bf16.bin", cfg, ln_jitter=0.3, bias_std=0.2)
+    lengths = np.array([5, 257, 64, 130], np.int32)
+    ids = np.random.default_rng(8).integers(0, cfg.vocab, int(lengths.sum())).astype(np.int32)
+    print("predict bf16 hidden 2048", flush=True)
+    check(model, ref, wl.pack_prompts(lengths, ids))
+
+
 def test_profile_hooks(tmp_models):
     """Kernel-family timing and the clock probe: plausible values, nothing left behind when off."""
     model, _ = make(tmp_models, "small_bf16.bin", SMALL, ln_jitter=0.1, bias_std=0.05)
