@@ -309,6 +309,33 @@ def main() -> int:
         out["router"] = {"requests": n_req, "instances": K_r, "window": l_r, "ms_per_batch": 1e3 * route_s,
                          "requests_per_s": n_req / route_s, "us_per_request": 1e6 * route_s / n_req}
 
+    # ---- scaler's checks over every instance's map, and the service workload forecasts (both small) ----
+    if args.stream_records > 0:
+        def timed(fn, reps=20):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            fn()
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e-3 / reps
+        K_s, L_s, win_s = 256, 4096, 100
+        rng = np.random.default_rng(12)
+        kv_s = t32(rng.integers(0, 400_000, K_s * L_s))
+        cap_s = t32(rng.integers(120_000, 400_001, K_s))
+        i32 = lambda n_: torch.empty(n_, dtype=torch.int32, device=dev)
+        oc, pk, ov, sm = i32(K_s), i32(K_s), i32(K_s), i32(2)
+        sd = torch.empty(1, dtype=torch.float64, device=dev)
+        scan_s = timed(lambda: ps.ps_scaler_scan(kv_s, cap_s, K_s, L_s, win_s, oc, pk, ov, sm, sd))
+        out["scaler"] = {"instances": K_s, "map_len": L_s, "window": win_s, "us_per_scan": 1e6 * scan_s}
+        fc = wl.make_forecaster_inputs(seed=0, n_services=512, hidden=64, k=24)
+        f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.float32).reshape(-1)).to(dev)
+        fw, fp, fd, fm = f32(fc.weights), f32(fc.hist_p), f32(fc.hist_d), f32(fc.mu)
+        fo = torch.empty(512 * 5, dtype=torch.float32, device=dev)
+        fc_s = timed(lambda: ps.ps_forecast(fw, 64, fp, fd, 512, 24, fm, fo))
+        out["forecaster"] = {"services": 512, "hidden": 64, "history": 24, "us_per_call": 1e6 * fc_s}
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = time_cpu_oracle(model_path, batch, ant)
     try:

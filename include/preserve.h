@@ -225,6 +225,7 @@ int ps_route(const int32_t* prompt_tokens, const int32_t* pred_tokens, int32_t n
  *            b_o[H] w_fx[H] W_fm[H][H] b_f[H] w_out[H] b_out scale, for the recurrence
  *              m = (w_mx x) * (W_mh h),  hh = w_hx x + W_hm m + b_h,  i, o, f = sigmoid(w_.x x + W_.m m + b_.),
  *              c = f c + i tanh(hh),  h = tanh(c) o;   x = count / scale;  forecast = max(0, scale (w_out . h + b_out))
+ *            each H x H matrix is stored input-major: the weight from input unit i to output unit j at [i * H + j];
  *            model 0 of a service is the prompt-token model, model 1 the response-token model
  *   hist_p, hist_d  [n_services][k] float: token counts of the k past windows, oldest first
  *   mu       [n_services][3] float: one instance's prefill, decode and total token capacity per window

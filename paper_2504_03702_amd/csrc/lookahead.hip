@@ -380,7 +380,9 @@ extern "C" int ps_route(const int32_t* prompt_tokens, const int32_t* pred_tokens
 // then the next time window from the k past windows (the recurrence goes on by one input, the first
 // forecast), and the forecasts give the number of instances N = max(P / mu_p, D / mu_d,
 // (P + D) / mu_t).  One wavefront per service, lane j owning hidden unit j (hidden <= 64); h and m
-// are exchanged through the wavefront's LDS slots; fp32 arithmetic.  A model is packed as
+// are exchanged through the wavefront's LDS slots; fp32 arithmetic.  Matrices are stored input-major
+// ([in][out]: element (out j, in i) at i * H + j), so the lanes of a wavefront read consecutive words.
+// A model is packed as
 //   w_mx[H] W_mh[H][H] w_hx[H] W_hm[H][H] b_h[H] w_ix[H] W_im[H][H] b_i[H] w_ox[H] W_om[H][H] b_o[H]
 //   w_fx[H] W_fm[H][H] b_f[H] w_out[H] b_out scale
 // ------------------------------------------------------------------------------------------------
@@ -425,7 +427,7 @@ __global__ __launch_bounds__(256) void forecast_kernel(const float* __restrict__
         for (int t = 0; t <= k; ++t) {
             const float x = (t < k ? hist[t] : y[kind][0]) / scale;
             float a = 0.f;
-            if (unit) for (int j = 0; j < H; ++j) a = fmaf(W_mh[lane * H + j], s_h[wave][j], a);
+            if (unit) for (int j = 0; j < H; ++j) a = fmaf(W_mh[j * H + lane], s_h[wave][j], a);
             s_m[wave][lane] = unit ? (w_mx[lane] * x) * a : 0.f;
             __syncthreads();
             if (unit) {
@@ -433,10 +435,10 @@ __global__ __launch_bounds__(256) void forecast_kernel(const float* __restrict__
                 float go = fmaf(w_ox[lane], x, b_o[lane]), gf = fmaf(w_fx[lane], x, b_f[lane]);
                 for (int j = 0; j < H; ++j) {
                     const float mj = s_m[wave][j];
-                    hh = fmaf(W_hm[lane * H + j], mj, hh);
-                    gi = fmaf(W_im[lane * H + j], mj, gi);
-                    go = fmaf(W_om[lane * H + j], mj, go);
-                    gf = fmaf(W_fm[lane * H + j], mj, gf);
+                    hh = fmaf(W_hm[j * H + lane], mj, hh);
+                    gi = fmaf(W_im[j * H + lane], mj, gi);
+                    go = fmaf(W_om[j * H + lane], mj, go);
+                    gf = fmaf(W_fm[j * H + lane], mj, gf);
                 }
                 c = sigmoid_f(gf) * c + sigmoid_f(gi) * tanhf(hh);
                 h = tanhf(c) * sigmoid_f(go);

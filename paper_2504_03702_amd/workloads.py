@@ -382,7 +382,8 @@ class ForecasterInputs:
         for n in FORECASTER_FIELDS:
             size = H * H if n.startswith("W_") else 1 if n in ("b_out", "scale") else H
             v = flat[at:at + size]
-            out[n] = v.reshape(H, H) if n.startswith("W_") else v[0] if size == 1 and n in ("b_out", "scale") else v
+            # matrices are stored input-major ([in][out]); the named arrays are [out][in]
+            out[n] = v.reshape(H, H).T.copy() if n.startswith("W_") else v[0] if size == 1 and n in ("b_out", "scale") else v
             at += size
         return out
 
