@@ -112,8 +112,8 @@ int ps_predict_load(ps_model* model, const int32_t* token_ids, const int32_t* of
                     float* pred_f, int32_t* pred_tokens,
                     void* workspace, size_t workspace_bytes, ps_status* status, void* hip_stream);
 
-/* Bytes of device workspace ps_anticipate() needs (partial curves of its workgroups).
- * 0 on invalid arguments. */
+/* Bytes of device workspace ps_anticipate() needs (partial curves of its workgroups, for both of its
+ * first kernels).  0 on invalid arguments. */
 size_t ps_anticipate_workspace_bytes(int64_t n_req, int32_t n_inst, int32_t horizon);
 
 /* Fold n_req predictions into the per-instance future-load curves (Sec. 3.4.1: the look-ahead
@@ -127,6 +127,10 @@ size_t ps_anticipate_workspace_bytes(int64_t n_req, int32_t n_inst, int32_t hori
  *             is persistent, the caller zeroes it to start afresh.
  *   overflow  [n_inst] int64, accumulated: tokens that fall at or after `horizon`.  May be NULL
  *             only if rate == NULL (nothing can overflow then).
+ *   Records may come in any order and the result does not depend on it.  Long streams (262144 records
+ *   or more, rate given, horizon <= 4096) whose records are in arrival order (non-decreasing
+ *   arrival_bucket, as in a request log) are folded by a cheaper kernel; if a record turns out to lie
+ *   outside the bucket window of its part of the stream, the general kernel redoes the call.
  *   workspace at least ps_anticipate_workspace_bytes(n_req, n_inst, horizon) bytes, 256-byte
  *             aligned.
  *   status    device ps_status or NULL.  Faulty records are skipped (PS_ST_BAD_RECORD).

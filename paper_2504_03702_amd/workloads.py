@@ -280,13 +280,15 @@ def make_anticipator_inputs(kind: str, seed: int = 0, n: Optional[int] = None,
         n_inst, horizon, with_rate, n = 4, 64, True, n or 64
     elif kind == "medium":
         n_inst, horizon, with_rate, n = 64, 600, True, n or 1024
-    elif kind in ("production", "stream"):
+    elif kind in ("production", "stream", "stream_by_arrival"):
         n_inst, horizon, with_rate = 256, 600, True
         n = n or (4096 if kind == "production" else 44_100_000)
     else:
         raise ValueError(kind)
     instance = rng.integers(0, n_inst, n, dtype=np.int32)
     arrival = rng.integers(0, horizon, n, dtype=np.int32)
+    if kind == "stream_by_arrival":
+        arrival.sort()                      # a request log: records in the order the requests arrive
     rate = rng.integers(30, 61, n_inst, dtype=np.int32) if with_rate else None
     if pred_tokens is None:
         pred_tokens = np.clip(np.rint(np.exp(rng.normal(np.log(87.0), 1.3, n))), 1, 4096).astype(np.int32)

@@ -36,6 +36,46 @@ def test_bit_exact(kind, n):
     assert np.array_equal(load.sum(axis=1, dtype=np.int64) + ovf, per_inst)
 
 
+@pytest.mark.parametrize("n", [262_144, 300_001, 3_000_001])
+def test_streams_in_arrival_order(n):
+    """Long streams in arrival order take the windowed first kernel (all instances, a window of
+    buckets per workgroup); the result is the same bit for bit."""
+    print(f"anticipator stream_by_arrival n={n}", flush=True)
+    inp = wl.make_anticipator_inputs("stream_by_arrival", seed=4, n=n)
+    load, ovf, flags = check(inp)
+    assert flags == 0
+    per_inst = np.bincount(inp.instance_id, weights=inp.pred_tokens, minlength=inp.n_inst).astype(np.int64)
+    assert np.array_equal(load.sum(axis=1, dtype=np.int64) + ovf, per_inst)
+    # the same records accumulated a second time into the first result, with an offset overflow
+    check(inp, load.copy(), ovf + 7)
+
+
+def test_arrival_order_with_exceptions():
+    """Streams that are almost in arrival order, or whose requests decode for longer than a window, make
+    the windowed kernel give up somewhere: the general kernel redoes the call, same result."""
+    rng = np.random.default_rng(9)
+    base = wl.make_anticipator_inputs("stream_by_arrival", seed=5, n=400_000)
+    # a handful of records far from their neighbours' buckets
+    a = base.arrival_bucket.copy()
+    a[rng.integers(0, a.size, 5)] = rng.integers(0, base.horizon, 5)
+    check(dataclasses.replace(base, arrival_bucket=a))
+    # slow instances: durations of hundreds of buckets, far beyond a window and the horizon
+    check(dataclasses.replace(base, rate=np.full(base.n_inst, 2, np.int32)))
+    # invalid records inside an ordered stream are skipped and the first one is named
+    k = base.instance_id.copy(); d = base.pred_tokens.copy(); a = base.arrival_bucket.copy()
+    k[1234] = base.n_inst; d[200_000] = -3; a[399_999] = base.horizon
+    _, _, flags = check(dataclasses.replace(base, instance_id=k, pred_tokens=d, arrival_bucket=a))
+    assert flags & ps.PS_ST_BAD_RECORD
+    # other shapes: few instances (a window as long as the horizon), many instances (a short window)
+    for n_inst, horizon in [(3, 100), (40, 4096), (1200, 600)]:
+        print(f"anticipator ordered K={n_inst} Hz={horizon}", flush=True)
+        n = 300_000
+        inp = wl.AnticipatorInputs(rng.integers(0, 3000, n, dtype=np.int32), rng.integers(0, n_inst, n, dtype=np.int32),
+                                   np.sort(rng.integers(0, horizon, n, dtype=np.int32)),
+                                   rng.integers(20, 200, n_inst, dtype=np.int32), n_inst, horizon)
+        check(inp)
+
+
 def test_accumulates_into_existing_map():
     inp = wl.make_anticipator_inputs("medium", seed=2, n=5000)
     rng = np.random.default_rng(0)
