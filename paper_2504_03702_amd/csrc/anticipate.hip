@@ -349,6 +349,7 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_window_kernel(
     __syncthreads();
     const bool bad_rate_rows = s_flag[0] != 0;               // uniform; rare
     unsigned long long mass = 0;       // bound on the magnitude any difference cell can have reached
+    unsigned mass32 = 0;               //   (a block's share, folded into it after the block)
     bool outside = false;
 
     // One record: (validity,) the two divisions, window test, three adds.  CHECKED is only used for
@@ -365,14 +366,14 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_window_kernel(
         }
         const unsigned dur = div_by_row((unsigned)D + (unsigned)rr.x - 1u, __int_as_float(rr.y));
         const unsigned qq = div_exact((unsigned)D, max(dur, 1u));         // D == 0: dur == 0, nothing is added
-        const unsigned rem = (unsigned)D - qq * dur;
+        const unsigned rem = (unsigned)D - __umul24(qq, dur);        // both below 2^16
         const unsigned room = (unsigned)horizon - (unsigned)a;     // buckets from a to the end of the row
         const unsigned rel = (unsigned)(a - a0);                    // wraps to a huge value before the window
         const unsigned reach = min(dur, room - 1u);                 // furthest bucket touched, from a
         const bool out = rel >= (unsigned)w_buckets || rel + reach >= (unsigned)w_buckets;
         outside |= out && D != 0;
         if (!out && D != 0) {
-            int* cell = s_diff + k * w_buckets + (int)rel;
+            int* cell = s_diff + __umul24((unsigned)k, (unsigned)w_buckets) + rel;   // (LDS holds the rows: both small)
             atomicAdd(cell, (int)(qq + (rem != 0)));                // rem == 0: the +1 and the -1 fall on the same cell
             if (rem != 0 && rem < room) atomicAdd(cell + rem, -1);
             if (dur < room) {
@@ -381,7 +382,7 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_window_kernel(
                 const unsigned long long inside = (unsigned long long)room * qq + min(room, rem);
                 atomicAdd(&s_ovf[k], (unsigned long long)D - inside);
             }
-            mass += qq + 1;
+            mass32 += qq + 1;
         }
     };
     using Checked = std::true_type;
@@ -419,6 +420,8 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_window_kernel(
 #pragma unroll
             for (int c = 0; c < 4; ++c) take(kk[c], dd[c], aa[c], rr[c], idx + c, true, Unchecked{});
         }
+        mass += mass32;
+        mass32 = 0;
     };
     const int64_t stride = (int64_t)kWaves * 256;
     const int64_t blk0 = begin + (int64_t)wave * 256;
@@ -449,6 +452,7 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_window_kernel(
                  (unsigned)k < (unsigned)n_inst ? s_rr[k] : make_int2(0, 0), idx + c, in, Checked{});
         }
     }
+    mass += mass32;
     if (__any(outside) && lane == 0) s_flag[1] = 1;
     for (int o = 32; o > 0; o >>= 1) mass += __shfl_xor(mass, o, 64);
     if (lane == 0 && mass >= (1ull << 31) / kWaves) report_fault(st, PS_ST_RANGE, begin);
