@@ -92,6 +92,7 @@ void plan_window(AntPlan& p, int64_t n, int n_inst, int horizon, bool with_rate)
     const int64_t fixed = 64 + (int64_t)n_inst * 16;             // flag + overflow + (rate, 1/rate)
     int64_t wb = (kLdsBytes - fixed) / ((int64_t)n_inst * 4);
     if (wb > horizon) wb = horizon;
+    if (wb < horizon) wb &= ~(int64_t)3;                          // whole 16-byte groups for the reduction's loads
     if (wb < 32) return;
     int64_t s = (n + kMinSlice - 1) / kMinSlice;
     if (s > kTargetWorkgroups) s = kTargetWorkgroups;
@@ -509,24 +510,55 @@ __global__ __launch_bounds__(kReduceThreads) void anticipate_reduce_kernel(
         const int64_t rstride = windowed ? (int64_t)row_len : (int64_t)n_inst * row_len;
         const int total = n_rows * row_len;                   // at most 256 * 4096
         const float inv_len = 1.0f / (float)row_len;
-        constexpr int NB = 16;                                // loads requested before the first is used
-        for (int e0 = tid; e0 < total; e0 += kReduceThreads * NB) {
-            int32_t v[NB];
-            int cell[NB];
+        if ((row_len & 3) == 0) {
+            // rows of whole 16-byte groups (every row then starts on a 16-byte boundary): four cells a load,
+            // all of a thread's loads requested before the first is used
+            const int groups = row_len >> 2, total4 = n_rows * groups;
+            const float inv_groups = 1.0f / (float)groups;
+            constexpr int NB = 12;
+            for (int e0 = tid; e0 < total4; e0 += kReduceThreads * NB) {
+                int4 v[NB];
+                int cell[NB];
 #pragma unroll
-            for (int u = 0; u < NB; ++u) {
-                const int e = min(e0 + kReduceThreads * u, total - 1);
-                int sl = (int)(((float)e + 0.5f) * inv_len);
-                int i = e - sl * row_len;
-                if (i < 0) { i += row_len; --sl; }
-                if (i >= row_len) { i -= row_len; ++sl; }
-                v[u] = rk[sl * rstride + i];
-                const int a0 = s_origin[sl];                  // -1: a slice that added nothing
-                cell[u] = (e0 + kReduceThreads * u < total && a0 >= 0 && a0 + i < horizon) ? a0 + i : -1;
+                for (int u = 0; u < NB; ++u) {
+                    const int e = min(e0 + kReduceThreads * u, total4 - 1);
+                    int sl = (int)(((float)e + 0.5f) * inv_groups);
+                    int g4 = e - sl * groups;
+                    if (g4 < 0) { g4 += groups; --sl; }
+                    if (g4 >= groups) { g4 -= groups; ++sl; }
+                    v[u] = *(const int4*)(rk + sl * rstride + 4 * g4);
+                    const int a0 = s_origin[sl];              // -1: a slice that added nothing
+                    cell[u] = (e0 + kReduceThreads * u < total4 && a0 >= 0) ? a0 + 4 * g4 : -1;
+                }
+#pragma unroll
+                for (int u = 0; u < NB; ++u) {
+                    if (cell[u] < 0) continue;
+                    const int x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (x[c] != 0 && cell[u] + c < horizon) atomicAdd(&s_row[cell[u] + c], (unsigned long long)(long long)x[c]);
+                }
             }
+        } else {
+            constexpr int NB = 16;                            // loads requested before the first is used
+            for (int e0 = tid; e0 < total; e0 += kReduceThreads * NB) {
+                int32_t v[NB];
+                int cell[NB];
 #pragma unroll
-            for (int u = 0; u < NB; ++u)
-                if (cell[u] >= 0 && v[u] != 0) atomicAdd(&s_row[cell[u]], (unsigned long long)(long long)v[u]);
+                for (int u = 0; u < NB; ++u) {
+                    const int e = min(e0 + kReduceThreads * u, total - 1);
+                    int sl = (int)(((float)e + 0.5f) * inv_len);
+                    int i = e - sl * row_len;
+                    if (i < 0) { i += row_len; --sl; }
+                    if (i >= row_len) { i -= row_len; ++sl; }
+                    v[u] = rk[sl * rstride + i];
+                    const int a0 = s_origin[sl];              // -1: a slice that added nothing
+                    cell[u] = (e0 + kReduceThreads * u < total && a0 >= 0 && a0 + i < horizon) ? a0 + i : -1;
+                }
+#pragma unroll
+                for (int u = 0; u < NB; ++u)
+                    if (cell[u] >= 0 && v[u] != 0) atomicAdd(&s_row[cell[u]], (unsigned long long)(long long)v[u]);
+            }
         }
         __syncthreads();
     }
