@@ -51,7 +51,10 @@ typedef struct ps_status {
 } ps_status;
 
 #define PS_ST_BAD_TOKEN    0x01  /* token id outside [0, vocab)                               */
-#define PS_ST_BAD_LENGTH   0x02  /* request length < 1, > its span, or + n_soft > max_pos     */
+#define PS_ST_BAD_LENGTH   0x02  /* request length < 1, > its span, or + n_soft > max_pos; a span
+                                    outside [0, n_tokens]; or overlapping spans that together need
+                                    more rows than n_tokens token slots can (the requests from the
+                                    first one that does not fit onwards)                      */
 #define PS_ST_NAN          0x04  /* a prediction is NaN                                       */
 #define PS_ST_BAD_RECORD   0x10  /* anticipator or look-ahead record skipped: pred_tokens < 0 or > PS_MAX_PRED,
                                     instance outside [0, n_inst), arrival outside [0, horizon),
@@ -91,7 +94,8 @@ size_t ps_workspace_bytes(const ps_model* model, int64_t max_tokens, int32_t max
 /* Predict the response length of n_req requests (Sec. 3.3).
  *   token_ids   [n_tokens] int32; request r's text tokens start at offsets[r]; the caller puts
  *               the [CLS] id first: the state of a request's first token is what is pooled.
- *   offsets     [n_req + 1] int32, non-decreasing, offsets[n_req] == n_tokens.
+ *   offsets     [n_req + 1] int32, non-decreasing, offsets[n_req] == n_tokens.  Checked on the device: a
+ *               request whose span breaks this is faulty (PS_ST_BAD_LENGTH), nothing is read out of bounds.
  *   lengths     NULL: packed layout, request r has offsets[r+1] - offsets[r] tokens.
  *               else [n_req]: padded layout, request r has lengths[r] valid tokens at the start
  *               of its span; the rest of the span is padding and takes no part in anything.

@@ -21,7 +21,7 @@
 //
 // Records in arrival order (a request log, the order requests are admitted in) allow a cheaper first
 // kernel, tried first on long streams: a slice of such a stream touches few buckets, so its workgroup
-// keeps a window of buckets for ALL instances in LDS (256 x 155 counters) instead of all buckets for a
+// keeps a window of buckets for ALL instances in LDS (256 x 152 counters) instead of all buckets for a
 // quarter of them.  Every record then belongs to the one workgroup that reads it: no second, third
 // and fourth inspection by other groups, no compaction queue.  A workgroup that meets a record
 // outside its window says so in place of its result; that makes the general kernel run after it
@@ -335,7 +335,10 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_window_kernel(
         if (tid == 0) worigin[slice] = -1;                    // nothing to add from this slice
         return;
     }
-    const int a0 = arrival_bucket[begin];
+    // window origin: the slice's first arrival bucket; a faulty (negative) one must not shift the window the
+    // slice's valid records are placed in, so the origin is never below bucket 0 (a first bucket at or beyond
+    // the horizon leaves every valid record before the window: the workgroup gives up and the general kernel runs)
+    const int a0 = max(arrival_bucket[begin], 0);
     if (tid < 2) s_flag[tid] = 0;
     __syncthreads();
     for (int i = tid; i < n_inst * w_buckets; i += kScatterThreads) s_diff[i] = 0;
@@ -473,7 +476,7 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_window_kernel(
         wpartial[((int64_t)k * gridDim.x + slice) * w_buckets + r] = s_diff[i];
     }
     for (int i = tid; i < n_inst; i += kScatterThreads) wovf[(int64_t)slice * n_inst + i] = (int64_t)s_ovf[i];
-    if (tid == 0) worigin[slice] = a0 < 0 ? -1 : a0;           // (a negative first bucket: nothing was added)
+    if (tid == 0) worigin[slice] = a0;
 }
 
 // One workgroup per instance.  Where the horizon is short enough for a 64-bit row of the map in LDS, all
@@ -643,10 +646,13 @@ extern "C" size_t ps_anticipate_workspace_bytes(int64_t n_req, int32_t n_inst, i
     return p.ok ? p.total_bytes : 0;
 }
 
-extern "C" int ps_anticipate(const int32_t* pred_tokens, const int32_t* instance_id,
-                             const int32_t* arrival_bucket, const int32_t* rate, int64_t n_req,
-                             int32_t n_inst, int32_t horizon, int32_t* load, int64_t* overflow,
-                             void* workspace, size_t workspace_bytes, ps_status* status, void* hip_stream) {
+namespace {
+
+// Validates the arguments and enqueues the kernels of one call on `s`, with `workspace` (device memory of at
+// least `workspace_bytes` bytes) for the partial curves.
+int anticipate_enqueue(const int32_t* pred_tokens, const int32_t* instance_id, const int32_t* arrival_bucket,
+                       const int32_t* rate, int64_t n_req, int32_t n_inst, int32_t horizon, int32_t* load,
+                       int64_t* overflow, void* workspace, size_t workspace_bytes, ps_status* status, hipStream_t s) {
     if (n_req < 0 || n_inst < 1 || horizon < 1 || !load) return PS_EINVAL;
     if (rate && !overflow) return PS_EINVAL;
     if (n_req == 0) return PS_OK;
@@ -663,7 +669,6 @@ extern "C" int ps_anticipate(const int32_t* pred_tokens, const int32_t* instance
     }
     plan_window(p, n_req, n_inst, horizon, rate != nullptr);
     if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < p.total_bytes) return PS_EWORKSPACE;
-    hipStream_t s = (hipStream_t)hip_stream;
     (void)hipGetLastError();
     static bool lds_attr_set = false;     // raising the limit twice is harmless, so no lock
     if (!lds_attr_set) {
@@ -695,4 +700,14 @@ extern "C" int ps_anticipate(const int32_t* pred_tokens, const int32_t* instance
     hipLaunchKernelGGL(anticipate_reduce_kernel, dim3((unsigned)n_inst), dim3(kReduceThreads), 0, s, partial, partial_ovf, p.slices, n_inst, horizon,
                        wpartial, wovf, worigin, p.w_slices, p.w_buckets, load, overflow, status);
     return hipGetLastError() == hipSuccess ? PS_OK : PS_EHIP;
+}
+
+}  // namespace
+
+extern "C" int ps_anticipate(const int32_t* pred_tokens, const int32_t* instance_id,
+                             const int32_t* arrival_bucket, const int32_t* rate, int64_t n_req,
+                             int32_t n_inst, int32_t horizon, int32_t* load, int64_t* overflow,
+                             void* workspace, size_t workspace_bytes, ps_status* status, void* hip_stream) {
+    return anticipate_enqueue(pred_tokens, instance_id, arrival_bucket, rate, n_req, n_inst, horizon, load, overflow,
+                              workspace, workspace_bytes, status, (hipStream_t)hip_stream);
 }

@@ -451,7 +451,7 @@ extern "C" int ps_predict_load(ps_model* m, const int32_t* token_ids, const int3
     (void)hipGetLastError();
     {
         ProfScope p(m, PS_FAM_EMBED, s);
-        launch_prep(m, offsets, lengths, n_req, ws, status, s);
+        launch_prep(m, offsets, lengths, n_req, n_tokens, ws, status, s);
         launch_embed(m, token_ids, offsets, n_req, ws, status, s);
     }
     if (m->info.dtype == 1) run_encoder_bf16(m, n_req, ws, s);

@@ -92,7 +92,7 @@ struct Workspace {
 Workspace plan_workspace(const ps_model_info& info, int64_t n_tokens, int32_t n_req, void* base);
 
 // ---- launchers (each enqueues on `s`; all pointers are device pointers) -------------------
-void launch_prep(const ps_model* m, const int32_t* offsets, const int32_t* lengths, int32_t n_req,
+void launch_prep(const ps_model* m, const int32_t* offsets, const int32_t* lengths, int32_t n_req, int64_t n_tokens,
                  const Workspace& ws, ps_status* st, hipStream_t s);
 void launch_embed(const ps_model* m, const int32_t* token_ids, const int32_t* offsets, int32_t n_req,
                   const Workspace& ws, ps_status* st, hipStream_t s);

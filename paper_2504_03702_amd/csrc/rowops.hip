@@ -8,26 +8,32 @@ namespace {
 // ------------------------------------------------------------------------------------------
 // prep: one workgroup turns (offsets, lengths) into the packed row layout of this call.
 // Request r occupies activation rows [row_start[r], row_start[r] + seq_len[r]); row_start is a
-// multiple of PS_ROW_ALIGN.  A request with an impossible length gets seq_len 0.
+// multiple of PS_ROW_ALIGN.  A request with an impossible length, or whose span leaves the
+// token array, gets seq_len 0.  The workspace was sized by the host for n_tokens token slots;
+// offsets that overlap can ask for more rows than that: requests from the first one that does
+// not fit onwards are dropped the same way, so no later kernel indexes past `row_capacity`.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ offsets,
                                                     const int32_t* __restrict__ lengths, int n_req,
-                                                    int n_soft, int max_pos, BatchMeta* meta,
+                                                    int n_soft, int max_pos, long long n_tokens,
+                                                    long long row_capacity, BatchMeta* meta,
                                                     int32_t* seq_len, int32_t* row_start,
                                                     int32_t* qtile_start, int32_t* bad_req,
                                                     ps_status* st) {
-    __shared__ int s_rows[1024];
-    __shared__ int s_tiles[1024];
+    __shared__ long long s_rows[1024];
+    __shared__ long long s_tiles[1024];
+    __shared__ long long s_cut_rows, s_cut_tiles;     // rows / query tiles in front of the first request that does not fit
     const int tid = threadIdx.x;
     const int per = (n_req + 1023) / 1024;
-    const int r0 = tid * per;
+    const int r0 = min(tid * per, n_req);
     const int r1 = min(r0 + per, n_req);
-    int rows = 0, tiles = 0;
+    long long rows = 0, tiles = 0;
     for (int r = r0; r < r1; ++r) {
-        const int span = offsets[r + 1] - offsets[r];
-        const int len = lengths ? lengths[r] : span;
-        const bool bad = span < 0 || len < 1 || len > span || len > max_pos - n_soft;
-        const int S = bad ? 0 : len + n_soft;
+        const long long o0 = offsets[r], o1 = offsets[r + 1];
+        const long long span = o1 - o0;
+        const long long len = lengths ? (long long)lengths[r] : span;
+        const bool bad = o0 < 0 || o1 > n_tokens || span < 0 || len < 1 || len > span || len > max_pos - n_soft;
+        const int S = bad ? 0 : (int)len + n_soft;
         if (bad) report_fault(st, PS_ST_BAD_LENGTH, r);
         seq_len[r] = S;
         bad_req[r] = 0;
@@ -39,28 +45,58 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t* __restrict__ 
     __syncthreads();
     // inclusive scan over the 1024 per-thread sums
     for (int d = 1; d < 1024; d <<= 1) {
-        int a = 0, b = 0;
+        long long a = 0, b = 0;
         if (tid >= d) { a = s_rows[tid - d]; b = s_tiles[tid - d]; }
         __syncthreads();
         s_rows[tid] += a;
         s_tiles[tid] += b;
         __syncthreads();
     }
-    int row = s_rows[tid] - rows, tile = s_tiles[tid] - tiles;
+    if (tid == 0) {
+        s_cut_rows = s_rows[1023];
+        s_cut_tiles = s_tiles[1023];
+    }
+    __syncthreads();
+    // Row starts are non-decreasing, so the requests that do not fit the workspace are a suffix: the first of
+    // them starts where the last fitting one ends.
+    long long row = s_rows[tid] - rows, tile = s_tiles[tid] - tiles;
+    bool cut_here = false;
+    long long my_cut_rows = 0, my_cut_tiles = 0;
     for (int r = r0; r < r1; ++r) {
-        row_start[r] = row;
-        qtile_start[r] = tile;
         const int S = seq_len[r];
-        row += (S + PS_ROW_ALIGN - 1) / PS_ROW_ALIGN * PS_ROW_ALIGN;
+        const long long sz = (S + PS_ROW_ALIGN - 1) / PS_ROW_ALIGN * PS_ROW_ALIGN;
+        if (row + sz > row_capacity) {
+            if (!cut_here && row <= row_capacity) { cut_here = true; my_cut_rows = row; my_cut_tiles = tile; }
+            if (S > 0) report_fault(st, PS_ST_BAD_LENGTH, r);
+            seq_len[r] = 0;
+            row_start[r] = -1;                       // set below, once the cut is known
+        } else {
+            row_start[r] = (int32_t)row;
+            qtile_start[r] = (int32_t)tile;
+        }
+        row += sz;
         tile += (S + PS_ATT_BQ - 1) / PS_ATT_BQ;
     }
+    // at most one thread holds the first request that does not fit with a start inside the capacity
+    if (cut_here) {
+        s_cut_rows = my_cut_rows;
+        s_cut_tiles = my_cut_tiles;
+    }
+    __syncthreads();
+    const long long cut_rows = min(s_cut_rows, row_capacity), cut_tiles = s_cut_tiles;
+    for (int r = r0; r < r1; ++r) {
+        if (row_start[r] < 0) {
+            row_start[r] = (int32_t)cut_rows;
+            qtile_start[r] = (int32_t)cut_tiles;
+        }
+    }
     if (tid == 1023) {
-        row_start[n_req] = s_rows[1023];
-        qtile_start[n_req] = s_tiles[1023];
-        meta->total_rows = s_rows[1023];
-        meta->total_qtiles = s_tiles[1023];
+        row_start[n_req] = (int32_t)cut_rows;
+        qtile_start[n_req] = (int32_t)cut_tiles;
+        meta->total_rows = (int32_t)cut_rows;
+        meta->total_qtiles = (int32_t)cut_tiles;
         meta->n_req = n_req;
-        meta->qkv_rows = s_rows[1023] + PS_KEY_SLACK;
+        meta->qkv_rows = (int32_t)cut_rows + PS_KEY_SLACK;
     }
 }
 
@@ -342,10 +378,11 @@ void launch_cls_gather(const ps_model* m, int32_t n_req, const Workspace& ws, co
                        m->info.hidden, n_req, ws.seq_len, ws.row_start, (bf16_t*)ws.cls_a);
 }
 
-void launch_prep(const ps_model* m, const int32_t* offsets, const int32_t* lengths, int32_t n_req,
+void launch_prep(const ps_model* m, const int32_t* offsets, const int32_t* lengths, int32_t n_req, int64_t n_tokens,
                  const Workspace& ws, ps_status* st, hipStream_t s) {
     hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(1024), 0, s, offsets, lengths, n_req, m->info.n_soft,
-                       m->info.max_pos, ws.meta, ws.seq_len, ws.row_start, ws.qtile_start, ws.bad_req, st);
+                       m->info.max_pos, (long long)n_tokens, (long long)(ws.max_rows - PS_KEY_SLACK), ws.meta, ws.seq_len,
+                       ws.row_start, ws.qtile_start, ws.bad_req, st);
 }
 
 void launch_embed(const ps_model* m, const int32_t* token_ids, const int32_t* offsets, int32_t n_req,

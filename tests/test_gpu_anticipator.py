@@ -66,6 +66,18 @@ def test_arrival_order_with_exceptions():
     k[1234] = base.n_inst; d[200_000] = -3; a[399_999] = base.horizon
     _, _, flags = check(dataclasses.replace(base, instance_id=k, pred_tokens=d, arrival_bucket=a))
     assert flags & ps.PS_ST_BAD_RECORD
+    # an invalid (negative) arrival bucket on the very first record, and on the first record of later parts of
+    # the stream (400 000 records are folded in 25 parts of 16 000): only those records may be dropped
+    for where in ([0], [16_000], [0, 16_000, 32_000, 384_000]):
+        print(f"anticipator ordered, negative first bucket at {where}", flush=True)
+        a = base.arrival_bucket.copy()
+        a[where] = [-2, -1, -7, -600][:len(where)]
+        got_load, got_ovf, flags = check(dataclasses.replace(base, arrival_bucket=a))
+        assert flags & ps.PS_ST_BAD_RECORD
+        keep = np.ones(a.size, bool)
+        keep[where] = False
+        per_inst = np.bincount(base.instance_id[keep], weights=base.pred_tokens[keep], minlength=base.n_inst).astype(np.int64)
+        assert np.array_equal(got_load.sum(axis=1, dtype=np.int64) + got_ovf, per_inst)
     # other shapes: few instances (a window as long as the horizon), many instances (a short window)
     for n_inst, horizon in [(3, 100), (40, 4096), (1200, 600)]:
         print(f"anticipator ordered K={n_inst} Hz={horizon}", flush=True)

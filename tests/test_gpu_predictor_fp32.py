@@ -107,6 +107,51 @@ def test_faulty_requests_are_isolated(tmp_models):
     assert flags == ps.PS_ST_BAD_LENGTH and np.isnan(f[0]) and t[0] == -1
 
 
+def test_wrong_offsets_are_rejected_on_the_device(tmp_models):
+    """Offsets are device data: spans that leave the token array, run backwards or overlap so that
+    together they ask for more rows than the workspace was sized for are flagged, their requests get
+    NaN / -1, and nothing is read or written out of bounds.  All buffers have the sizes the call states."""
+    model, _ = make(tmp_models, "tiny_gpu.bin")
+    b = wl.make_prompts("tiny", 8, n_req=6)
+    good_f, good_t, _, _ = run_predict(model, b)
+    n_tok = int(b.offsets[-1])
+    # request 1 starts before the array, request 4 ends after it
+    offs = b.offsets.copy()
+    offs[1] = -3
+    f, t, flags, first = run_predict(model, dataclasses.replace(b, offsets=offs))
+    assert flags == ps.PS_ST_BAD_LENGTH and first == 0        # span 0 ends at -3 < its start
+    assert np.isnan(f[[0, 1]]).all() and (t[[0, 1]] == -1).all()
+    assert np.array_equal(f[2:], good_f[2:])
+    offs = b.offsets.copy()
+    offs[5] = n_tok + 40                                       # request 4 runs past the end, request 5 starts there
+    f, t, flags, first = run_predict(model, dataclasses.replace(b, offsets=offs))
+    assert flags == ps.PS_ST_BAD_LENGTH and first == 4
+    assert np.isnan(f[[4, 5]]).all() and np.array_equal(f[:4], good_f[:4])
+    # offsets 0, span, 0, span, ...: every even request claims the same valid span [0, span), every odd one runs
+    # backwards.  Each even request is valid on its own; together they need several times the rows the host
+    # planned for from the size of the token array
+    import torch
+    span = min(TINY.max_pos, n_tok)
+    n_req = 40
+    offs = np.tile(np.array([0, span], np.int32), n_req)[: n_req + 1].copy()
+    dev = "cuda:0"
+    ids = torch.from_numpy(b.token_ids).to(dev)
+    pf = torch.full((n_req,), 5.0, dtype=torch.float32, device=dev)
+    pt = torch.full((n_req,), -7, dtype=torch.int32, device=dev)
+    ws = ps.alloc_workspace(ps.ps_workspace_bytes(model, n_tok, n_req), dev)
+    st = ps.new_status(dev)
+    ps.ps_predict_load(model, ids, torch.from_numpy(offs).to(dev), None, pf, pt, ws, st)
+    flags, first = ps.ps_status_read(st)
+    f, t = pf.cpu().numpy(), pt.cpu().numpy()
+    assert flags == ps.PS_ST_BAD_LENGTH and first == 1
+    assert np.isnan(f[1::2]).all() and (t[1::2] == -1).all()
+    even = f[0::2]
+    n_ok = int(np.sum(~np.isnan(even)))
+    assert 1 <= n_ok < even.size and not np.isnan(even[:n_ok]).any() and np.isnan(even[n_ok:]).all()
+    assert np.all(even[:n_ok] == even[0])                      # the same prompt every time
+    assert (t[0::2][n_ok:] == -1).all()
+
+
 def test_host_side_argument_errors(tmp_models):
     import torch
     model, _ = make(tmp_models, "tiny_gpu.bin")
