@@ -148,6 +148,22 @@ int ps_anticipate(const int32_t* pred_tokens, const int32_t* instance_id,
                   int32_t* load, int64_t* overflow,
                   void* workspace, size_t workspace_bytes, ps_status* status, void* hip_stream);
 
+/* ps_anticipate() for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, result and errors as
+ * ps_anticipate() without `workspace`: the partial curves go to an array of PS_ANTICIPATE_STATIC_BYTES bytes
+ * that is part of the library's device image (every GPU the library runs on holds its copy until the process
+ * ends).  The call allocates and frees nothing.  Calls whose ps_anticipate_workspace_bytes() exceeds the
+ * array are refused with PS_EWORKSPACE (with 256 instances x 600 buckets the array holds calls of up to
+ * 212992 records; the long request-log streams need ps_anticipate()).  The device is the calling thread's
+ * current one, and `hip_stream` must belong to it.  All calls on one GPU share that GPU's array: the caller
+ * orders them (one stream, or events); calls that overlap on one GPU race on it.  Nothing needs clearing
+ * between calls: the kernels write every scratch cell they later read. */
+#define PS_ANTICIPATE_STATIC_BYTES  (8u << 20)
+int ps_anticipate_static(const int32_t* pred_tokens, const int32_t* instance_id,
+                         const int32_t* arrival_bucket, const int32_t* rate,
+                         int64_t n_req, int32_t n_inst, int32_t horizon,
+                         int32_t* load, int64_t* overflow, ps_status* status, void* hip_stream);
+
 /* The load-look-ahead map in the paper's own units (Sec. 3.4.1): kv_tokens[k][t] is the number of
  * KV-cache tokens instance k is expected to hold at the t-th decoding iteration from now (the paper
  * records U = tokens / M, the fraction of the instance's token capacity M; see `fraction` below).

@@ -20,7 +20,7 @@ PS_ERRORS = {-1: "PS_EINVAL", -2: "PS_EIO", -3: "PS_EFORMAT", -4: "PS_ENOMEM", -
 PS_ST_BAD_TOKEN, PS_ST_BAD_LENGTH, PS_ST_NAN, PS_ST_BAD_RECORD, PS_ST_RANGE = 0x01, 0x02, 0x04, 0x10, 0x20
 
 EXPORTS = ["ps_model_load", "ps_model_free", "ps_model_get_info", "ps_workspace_bytes", "ps_predict_load",
-           "ps_anticipate_workspace_bytes", "ps_anticipate", "ps_status_read", "ps_strerror",
+           "ps_anticipate_workspace_bytes", "ps_anticipate", "ps_anticipate_static", "ps_status_read", "ps_strerror",
            "ps_profile_enable", "ps_profile_read", "ps_profile_clock",
            "ps_lookahead_workspace_bytes", "ps_lookahead_update", "ps_scaler_scan", "ps_route", "ps_forecast"]
 PS_FAMILIES = ["embed", "gemm", "attention", "layernorm", "head", "refine"]
@@ -67,6 +67,8 @@ def load_library() -> ctypes.CDLL:
     lib.ps_anticipate_workspace_bytes.argtypes = [i64, i32, i32]
     lib.ps_anticipate.restype = ctypes.c_int
     lib.ps_anticipate.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp, vp]
+    lib.ps_anticipate_static.restype = ctypes.c_int
+    lib.ps_anticipate_static.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp]
     lib.ps_lookahead_workspace_bytes.restype = sz
     lib.ps_lookahead_workspace_bytes.argtypes = [i32, i32]
     lib.ps_lookahead_update.restype = ctypes.c_int
@@ -203,6 +205,25 @@ def ps_anticipate(pred_tokens: torch.Tensor, instance_id: torch.Tensor, arrival_
         pred_tokens.numel(), n_inst, horizon, _ptr(load, torch.int32, "load"),
         _ptr(overflow, torch.int64, "overflow"), _ptr(workspace, torch.uint8, "workspace"),
         workspace.numel(), _ptr(status, torch.int64, "status"), _stream()), "ps_anticipate")
+
+
+PS_ANTICIPATE_STATIC_BYTES = 8 << 20
+
+
+def ps_anticipate_static(pred_tokens: torch.Tensor, instance_id: torch.Tensor, arrival_bucket: torch.Tensor,
+                         rate: Optional[torch.Tensor], n_inst: int, horizon: int, load: torch.Tensor,
+                         overflow: Optional[torch.Tensor], status: Optional[torch.Tensor] = None) -> None:
+    """ps_anticipate without a workspace argument: the library's own fixed device array holds the partial curves."""
+    if load.numel() != n_inst * horizon or (overflow is not None and overflow.numel() != n_inst) or \
+            (rate is not None and rate.numel() != n_inst) or \
+            instance_id.numel() != pred_tokens.numel() or arrival_bucket.numel() != pred_tokens.numel():
+        raise ValueError("ps_anticipate_static: array sizes do not match n_req / n_inst / horizon")
+    _check(load_library().ps_anticipate_static(
+        _ptr(pred_tokens, torch.int32, "pred_tokens"), _ptr(instance_id, torch.int32, "instance_id"),
+        _ptr(arrival_bucket, torch.int32, "arrival_bucket"), _ptr(rate, torch.int32, "rate"),
+        pred_tokens.numel(), n_inst, horizon, _ptr(load, torch.int32, "load"),
+        _ptr(overflow, torch.int64, "overflow"), _ptr(status, torch.int64, "status"), _stream()),
+        "ps_anticipate_static")
 
 
 def ps_lookahead_workspace_bytes(n_inst: int, map_len: int) -> int:

@@ -29,6 +29,7 @@
 // the outcome is the same for any order.
 #include <string.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "device_util.h"
@@ -710,4 +711,43 @@ extern "C" int ps_anticipate(const int32_t* pred_tokens, const int32_t* instance
                              void* workspace, size_t workspace_bytes, ps_status* status, void* hip_stream) {
     return anticipate_enqueue(pred_tokens, instance_id, arrival_bucket, rate, n_req, n_inst, horizon, load, overflow,
                               workspace, workspace_bytes, status, (hipStream_t)hip_stream);
+}
+
+// ---- the variant for callers that cannot allocate ---------------------------------------------------------
+// Its partial curves live in a file-scope device array instead of a caller-provided workspace.  Every GPU the
+// library runs on holds its own copy of the array at its own address: the address is looked up once per
+// device and kept; host code only ever uses that address, never the array's name.
+static __device__ __align__(256) unsigned char scratch[PS_ANTICIPATE_STATIC_BYTES];
+
+namespace {
+const int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices];       // per device: device address of `scratch`, null until looked up
+}  // namespace
+
+extern "C" int ps_anticipate_static(const int32_t* pred_tokens, const int32_t* instance_id,
+                                    const int32_t* arrival_bucket, const int32_t* rate, int64_t n_req,
+                                    int32_t n_inst, int32_t horizon, int32_t* load, int64_t* overflow,
+                                    ps_status* status, void* hip_stream) {
+    if (n_req < 0 || n_inst < 1 || horizon < 1) return PS_EINVAL;
+    // sizes beyond the array are refused before anything else is looked at
+    const size_t need = ps_anticipate_workspace_bytes(n_req, n_inst, horizon);
+    if (need == 0) return PS_EUNSUPPORTED;
+    if (need > (size_t)PS_ANTICIPATE_STATIC_BYTES) return PS_EWORKSPACE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return PS_EHIP;
+    if (dev < 0 || dev >= kMaxDevices) return PS_EUNSUPPORTED;
+    void* ptr;
+    {
+        std::lock_guard<std::mutex> hold(g_scratch_lock);
+        if (!g_scratch_ptr[dev]) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PS_EHIP;
+            g_scratch_ptr[dev] = p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    // the kernels write every partial cell they later read, so the last call's contents need no clearing
+    return anticipate_enqueue(pred_tokens, instance_id, arrival_bucket, rate, n_req, n_inst, horizon, load, overflow,
+                              ptr, (size_t)PS_ANTICIPATE_STATIC_BYTES, status, (hipStream_t)hip_stream);
 }
