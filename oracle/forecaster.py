@@ -6,17 +6,23 @@ instances.
 TEST INFRASTRUCTURE ONLY: the plain definition the GPU library is checked against.  It shares no
 code with the GPU path; only tests, the smoke check and the benchmark's CPU-baseline leg may call it.
 
+A model sees its input sequence min-max normalised (Alg. 1's normalisation step, the form the models
+are trained on):  x_t = (v_t - min v) / (max v - min v)  over the sequence it is given, and its
+output is taken back to token counts with the same two numbers:  forecast = min v + (max v - min v) y,
+not below 0.  A flat sequence (max v = min v) takes the range as 1.
+
 The recurrence is the multiplicative LSTM of Krause et al. (2016), which the paper names: with scalar
-input x_t (a window's token count divided by the model's `scale`), hidden state h and cell c,
+input x_t, hidden state h and cell c,
     m_t = (w_mx x_t) * (W_mh h_{t-1})                      elementwise product
     hh  = w_hx x_t + W_hm m_t + b_h
     i_t = sigmoid(w_ix x_t + W_im m_t + b_i),  o_t, f_t likewise
     c_t = f_t * c_{t-1} + i_t * tanh(hh)
     h_t = tanh(c_t) * o_t
-and the forecast after the last input is  y = scale * (w_out . h + b_out), not below 0.
-Online phase (Alg. 2): step 1 forecasts the current window from the k past windows; the forecast is
-appended to the history and step 2 forecasts the next window from the k + 1 values (the recurrence
-simply goes on by one input).  With both kinds forecast, prompt tokens P and response tokens D,
+and the model's output after the last input is  y = w_out . h + b_out.
+Online phase (Alg. 2): step 1 applies the model to the k past windows and gives the forecast of the
+current window; that forecast is appended to the history and step 2 applies the model to the k + 1
+values (normalised over those k + 1 values) for the next window.  With both kinds forecast, prompt
+tokens P and response tokens D,
     N = max(P / mu_p, D / mu_d, (P + D) / mu_t)
 for the instance's profiled prefill, decode and total token capacities per window."""
 from __future__ import annotations
@@ -24,7 +30,7 @@ from __future__ import annotations
 import numpy as np
 
 NAMES = ("w_mx", "W_mh", "w_hx", "W_hm", "b_h", "w_ix", "W_im", "b_i", "w_ox", "W_om", "b_o", "w_fx", "W_fm", "b_f",
-         "w_out", "b_out", "scale")
+         "w_out", "b_out")
 
 
 def sigmoid(z):
@@ -41,20 +47,31 @@ def mlstm_step(w, x, h, c):
     return np.tanh(c) * o, c
 
 
-def readout(w, h):
-    return max(0.0, float(w["scale"]) * (float(w["w_out"] @ h) + float(w["b_out"])))
+def normalise(seq):
+    """Alg. 1's normalisation of one input sequence: (normalised values, minimum, range)."""
+    seq = np.asarray(seq, np.float64)
+    lo, hi = float(seq.min()), float(seq.max())
+    span = hi - lo if hi > lo else 1.0
+    return (seq - lo) / span, lo, span
+
+
+def model_forecast(w, seq):
+    """The model applied to one sequence of token counts: normalise, run the recurrence, read out, de-normalise."""
+    w = {k: np.asarray(v, np.float64) for k, v in w.items()}
+    x, lo, span = normalise(seq)
+    hm = w["W_mh"].shape[0]
+    h, c = np.zeros(hm), np.zeros(hm)
+    for xt in x:
+        h, c = mlstm_step(w, xt, h, c)
+    y = float(w["w_out"] @ h) + float(w["b_out"])
+    return max(0.0, lo + span * y)
 
 
 def two_step_forecast(w, history):
     """(forecast of the current window, forecast of the next window) from the k past windows."""
-    w = {k: np.asarray(v, np.float64) for k, v in w.items()}
-    hm = w["W_mh"].shape[0]
-    h, c = np.zeros(hm), np.zeros(hm)
-    for v in np.asarray(history, np.float64):
-        h, c = mlstm_step(w, v / float(w["scale"]), h, c)
-    y1 = readout(w, h)
-    h, c = mlstm_step(w, y1 / float(w["scale"]), h, c)
-    return y1, readout(w, h)
+    history = np.asarray(history, np.float64)
+    y1 = model_forecast(w, history)
+    return y1, model_forecast(w, np.append(history, y1))
 
 
 def forecast_services(models_p, models_d, hist_p, hist_d, mu_p, mu_d, mu_t):
