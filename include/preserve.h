@@ -244,11 +244,15 @@ int ps_route(const int32_t* prompt_tokens, const int32_t* pred_tokens, int32_t n
  * forecast the token count of the current time window from the counts of the k past windows, then,
  * with that forecast appended to the history, the count of the next window; the next window's
  * counts give the number of instances  N = max(P / mu_p, D / mu_d, (P + D) / mu_t).
- *   weights  [n_services][2][5 H^2 + 10 H + 2] float, H = hidden <= 64; per model, in this order:
+ *   weights  [n_services][2][5 H^2 + 10 H + 1] float, H = hidden <= 64; per model, in this order:
  *            w_mx[H] W_mh[H][H] w_hx[H] W_hm[H][H] b_h[H] w_ix[H] W_im[H][H] b_i[H] w_ox[H] W_om[H][H]
- *            b_o[H] w_fx[H] W_fm[H][H] b_f[H] w_out[H] b_out scale, for the recurrence
+ *            b_o[H] w_fx[H] W_fm[H][H] b_f[H] w_out[H] b_out, for the recurrence
  *              m = (w_mx x) * (W_mh h),  hh = w_hx x + W_hm m + b_h,  i, o, f = sigmoid(w_.x x + W_.m m + b_.),
- *              c = f c + i tanh(hh),  h = tanh(c) o;   x = count / scale;  forecast = max(0, scale (w_out . h + b_out))
+ *              c = f c + i tanh(hh),  h = tanh(c) o
+ *            on the input sequence min-max normalised as in Alg. 1: x = (count - min) / (max - min) over the
+ *            sequence the model is applied to (a flat sequence takes the range as 1), and
+ *            forecast = max(0, min + (max - min) (w_out . h + b_out)).  The second step's sequence is the k
+ *            past windows plus the first forecast, normalised over those k + 1 values.
  *            each H x H matrix is stored input-major: the weight from input unit i to output unit j at [i * H + j];
  *            model 0 of a service is the prompt-token model, model 1 the response-token model
  *   hist_p, hist_d  [n_services][k] float: token counts of the k past windows, oldest first

@@ -285,7 +285,7 @@ def ps_route(prompt_tokens: torch.Tensor, pred_tokens: torch.Tensor, n_inst: int
 
 def ps_forecast(weights: torch.Tensor, hidden: int, hist_p: torch.Tensor, hist_d: torch.Tensor, n_services: int,
                 k: int, mu: torch.Tensor, out: torch.Tensor) -> None:
-    if weights.numel() != n_services * 2 * (5 * hidden * hidden + 10 * hidden + 2) or hist_p.numel() != n_services * k or \
+    if weights.numel() != n_services * 2 * (5 * hidden * hidden + 10 * hidden + 1) or hist_p.numel() != n_services * k or \
             hist_d.numel() != n_services * k or mu.numel() != 3 * n_services or out.numel() != 5 * n_services:
         raise ValueError("ps_forecast: array sizes do not match n_services / hidden / k")
     _check(load_library().ps_forecast(

@@ -365,13 +365,13 @@ def make_lookahead_inputs(kind: str, seed: int = 0, n: Optional[int] = None,
 
 
 FORECASTER_FIELDS = ("w_mx", "W_mh", "w_hx", "W_hm", "b_h", "w_ix", "W_im", "b_i", "w_ox", "W_om", "b_o", "w_fx", "W_fm",
-                     "b_f", "w_out", "b_out", "scale")
+                     "b_f", "w_out", "b_out")
 
 
 @dataclasses.dataclass
 class ForecasterInputs:
     """Models and histories of the service workload predictor (paper Sec. 3.2)."""
-    weights: np.ndarray           # [n_services, 2, 5 H^2 + 10 H + 2] float32, fields in FORECASTER_FIELDS order
+    weights: np.ndarray           # [n_services, 2, 5 H^2 + 10 H + 1] float32, fields in FORECASTER_FIELDS order
     hist_p: np.ndarray            # [n_services, k] float32 prompt tokens per past window
     hist_d: np.ndarray            # [n_services, k] float32 response tokens per past window
     mu: np.ndarray                # [n_services, 3] float32 per-instance capacities (prefill, decode, total)
@@ -382,21 +382,22 @@ class ForecasterInputs:
         """Model `kind` (0 prompt, 1 response) of service s as named float64 arrays."""
         H, flat, at, out = self.hidden, self.weights[s, kind].astype(np.float64), 0, {}
         for n in FORECASTER_FIELDS:
-            size = H * H if n.startswith("W_") else 1 if n in ("b_out", "scale") else H
+            size = H * H if n.startswith("W_") else 1 if n == "b_out" else H
             v = flat[at:at + size]
             # matrices are stored input-major ([in][out]); the named arrays are [out][in]
-            out[n] = v.reshape(H, H).T.copy() if n.startswith("W_") else v[0] if size == 1 and n in ("b_out", "scale") else v
+            out[n] = v.reshape(H, H).T.copy() if n.startswith("W_") else v[0] if n == "b_out" else v
             at += size
         return out
 
 
 def make_forecaster_inputs(seed: int = 0, n_services: int = 8, hidden: int = 32, k: int = 12) -> ForecasterInputs:
-    """Random-init models (N(0, 0.3) matrices, N(0, 0.5) vectors, readout bias 0.5) and histories shaped
-    like the paper's traces: token counts per 10-minute window following a daily cycle with noise,
-    prompt tokens around 4e6 and response tokens around 2e6 per window, scaled by 1e7 inside the model."""
+    """Random-init models (N(0, 0.3) matrices, N(0, 0.5) vectors, read-out weights N(0, 0.5) and bias 0.5, so that
+    first forecasts fall inside the history's range for some services and outside it for others) and histories
+    shaped like the paper's traces: token counts per 10-minute window following a daily cycle with noise, prompt
+    tokens around 4e6 and response tokens around 2e6 per window."""
     rng = np.random.default_rng(seed + 7000)
     H = hidden
-    per_model = 5 * H * H + 10 * H + 2
+    per_model = 5 * H * H + 10 * H + 1
     w = np.zeros((n_services, 2, per_model), np.float32)
     for s in range(n_services):
         for kind in range(2):
@@ -406,8 +407,6 @@ def make_forecaster_inputs(seed: int = 0, n_services: int = 8, hidden: int = 32,
                     parts.append(rng.normal(0, 0.3, H * H))
                 elif n == "b_out":
                     parts.append(np.array([0.5]))
-                elif n == "scale":
-                    parts.append(np.array([1e7]))
                 else:
                     parts.append(rng.normal(0, 0.5, H))
             w[s, kind] = np.concatenate(parts).astype(np.float32)

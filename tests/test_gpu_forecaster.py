@@ -35,6 +35,11 @@ def test_forecasts_and_instance_counts(S, H, k):
     print(f"  max rel err {err.max():.2e}", flush=True)
     assert err.max() < TOL
     assert np.std(ref[2]) > 0 or S == 1                      # services differ
+    if S >= 8:
+        # both kinds of second step occur: first forecast inside the history's range (recurrence carried on) and
+        # outside it (extended history normalised afresh)
+        inside = (ref[0] >= x.hist_p.min(axis=1)) & (ref[0] <= x.hist_p.max(axis=1))
+        assert inside.any() and (~inside).any()
 
 
 def test_argument_checks():
