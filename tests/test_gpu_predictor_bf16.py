@@ -9,6 +9,7 @@ import pytest
 from oracle import predictor as op
 from paper_2504_03702_amd import binding as ps
 from paper_2504_03702_amd import workloads as wl
+from tests import oracle_pool
 from tests.gpu_util import TOL_BF16, rel_err, run_predict
 
 pytestmark = pytest.mark.gpu
@@ -117,27 +118,69 @@ def test_bert_base_padded_batch(tmp_models):
     check(model, ref, batch)
 
 
-def test_bert_base_varlen_sampled(tmp_models):
-    """The 1024-prompt packed batch runs whole on the GPU; the oracle checks a sample of requests
-    (a request's prediction does not depend on the rest of the batch)."""
-    print("predict bf16 bert_base varlen 1024", flush=True)
+def requests_of(batch, picks):
+    return [batch.token_ids[batch.offsets[r]:batch.offsets[r + 1]] for r in picks]
+
+
+def stratified(lengths, candidates, count):
+    """`count` of the candidate requests spread evenly over their length ranks (shortest and longest included)."""
+    by_len = candidates[np.argsort(lengths[candidates], kind="stable")]
+    return by_len[np.unique(np.linspace(0, len(by_len) - 1, count).round().astype(np.int64))]
+
+
+def check_against_pool(tag, model_path, batch, got_f, got_t, picks, d_max):
+    """Oracle (one request at a time, on the host's cores) against the GPU's predictions for `picks`."""
+    ref_f = oracle_pool.predict_requests(model_path, requests_of(batch, picks))
+    # the scale of the tolerance is the batch's RMS; the RMS over these hundreds of requests stands in for it
+    scale = np.maximum(np.abs(ref_f), np.sqrt(np.mean(ref_f ** 2)))
+    err = np.abs(got_f[picks] - ref_f) / scale
+    worst = int(np.argmax(err))
+    lengths = batch.valid_lengths()
+    print(f"  {tag}: {len(picks)} requests, {int(lengths[picks].sum())} tokens: max rel err {err.max():.3e} "
+          f"(request {int(picks[worst])}, {int(lengths[picks[worst]])} tokens), p99 {np.quantile(err, 0.99):.3e}, "
+          f"mean {err.mean():.3e}", flush=True)
+    assert err.max() < TOL_BF16
+    ref_t = np.clip(np.rint(ref_f), 0, d_max).astype(np.int32)
+    assert np.all(np.abs(got_t[picks] - ref_t) <= np.ceil(TOL_BF16 * scale) + 1)
+
+
+def chunks_bit_equal(model, batch, got_f, got_t, chunk=256):
+    """The same requests in calls of `chunk` requests each (other row counts, other tile walks): bit-equal."""
+    lengths = batch.valid_lengths()
+    for r0 in range(0, batch.n_req, chunk):
+        picks = np.arange(r0, min(r0 + chunk, batch.n_req))
+        sub = wl.pack_prompts(lengths[picks], np.concatenate(requests_of(batch, picks)))
+        f, t, flags, _ = run_predict(model, sub)
+        assert flags == 0 and np.array_equal(f, got_f[picks]) and np.array_equal(t, got_t[picks]), f"chunk at {r0}"
+
+
+@pytest.fixture(scope="module")
+def bert_varlen(tmp_models):
     cfg = wl.MODELS["bert_base"]
-    model, ref = make(tmp_models, "bert_base.bin", cfg)
+    model, _ = make(tmp_models, "bert_base.bin", cfg)
     batch = wl.make_prompts("bert_base_varlen", seed=0)
     got_f, got_t, flags, _ = run_predict(model, batch)
     assert flags == 0 and np.isfinite(got_f).all()
+    return model, os.path.join(tmp_models, "bert_base.bin"), batch, got_f, got_t
+
+
+def test_bert_base_varlen_chunks_bit_equal(bert_varlen):
+    """The 1024-prompt packed batch runs whole on the GPU; the same requests in four calls of 256 give the same
+    bits (a request's prediction does not depend on the rest of the batch, nor on where its rows fall)."""
+    print("predict bf16 bert_base varlen 1024: whole batch against chunks of 256", flush=True)
+    model, _, batch, got_f, got_t = bert_varlen
+    chunks_bit_equal(model, batch, got_f, got_t)
+
+
+def test_bert_base_varlen_against_oracle(bert_varlen):
+    """Every request of at most 48 tokens (short prompts carry the largest errors) and 64 others spread evenly
+    over the length ranks, each against the oracle."""
+    print("predict bf16 bert_base varlen 1024: short prompts and a length-stratified sample against the oracle", flush=True)
+    model, path, batch, got_f, got_t = bert_varlen
     lengths = batch.valid_lengths()
-    pick = np.unique(np.concatenate([[0, 1023, int(np.argmax(lengths)), int(np.argmin(lengths))],
-                                     np.random.default_rng(0).choice(1024, 20, replace=False)]))
-    sub = wl.pack_prompts(lengths[pick], np.concatenate([batch.token_ids[batch.offsets[r]:batch.offsets[r + 1]] for r in pick]))
-    ref_f, _ = op.predict_load(ref, sub.token_ids, sub.offsets)
-    scale = np.maximum(np.abs(ref_f), np.sqrt(np.mean(ref_f ** 2)))
-    err = np.abs(got_f[pick] - ref_f) / scale
-    print(f"  max rel err {err.max():.3e} mean {err.mean():.3e}", flush=True)
-    assert err.max() < TOL_BF16
-    # the same requests alone give bit-identical results: no cross-request leakage
-    alone_f, _, _, _ = run_predict(model, sub)
-    assert np.array_equal(alone_f, got_f[pick])
+    short = np.flatnonzero(lengths <= 48)
+    rest = stratified(lengths, np.flatnonzero(lengths > 48), 64)
+    check_against_pool("short + stratified", path, batch, got_f, got_t, np.concatenate([short, rest]), model.info.d_max)
 
 
 def test_latency_shape_micro_batches(tmp_models):
@@ -149,17 +192,13 @@ def test_latency_shape_micro_batches(tmp_models):
         check(model, ref, wl.make_prompts("latency", seed=seed))
 
 
-def test_production_batch_sampled_and_fused_anticipator(tmp_models):
-    """The benchmark's own launch configuration: 16-layer H1024 encoder, 4096 packed prompts up to
-    2048 tokens, then ps_anticipate over 256 x 600 on the predictions, same stream.  The oracle checks
-    a sample of requests one by one (the longest, the shortest, the first, the last and random ones);
-    the histograms are checked bit-exact against the oracle fed the GPU's own integer predictions, and
-    the totals invariant holds on everything."""
+@pytest.fixture(scope="module")
+def production(tmp_models):
+    """The benchmark's own launch configuration: 16-layer H1024 encoder, 4096 packed prompts up to 2048 tokens,
+    then ps_anticipate over 256 x 600 on the predictions, same stream."""
     import torch
-    from oracle import anticipator as oa
-    print("predict bf16 production 4096 + anticipator", flush=True)
     cfg = wl.MODELS["production"]
-    model, ref = make(tmp_models, "production.bin", cfg)
+    model, _ = make(tmp_models, "production.bin", cfg)
     batch = wl.make_prompts("production", seed=0)
     n = batch.n_req
     dev = "cuda:0"
@@ -179,25 +218,52 @@ def test_production_batch_sampled_and_fused_anticipator(tmp_models):
     ps.ps_anticipate(pred_t, inst, arr, rate, ant.n_inst, ant.horizon, load, ovf, aws, st)
     flags, _ = ps.ps_status_read(st)
     assert flags == 0
-    got_f, got_t = pred_f.cpu().numpy(), pred_t.cpu().numpy()
+    return dict(model=model, path=os.path.join(tmp_models, "production.bin"), batch=batch, ant=ant,
+                got_f=pred_f.cpu().numpy(), got_t=pred_t.cpu().numpy(),
+                load=load.cpu().numpy().reshape(ant.n_inst, ant.horizon), ovf=ovf.cpu().numpy())
+
+
+def test_production_batch_fused_anticipator(production):
+    """The histograms are bit-exact against the oracle fed the GPU's own integer predictions, and the totals
+    invariant holds on everything."""
+    from oracle import anticipator as oa
+    print("predict bf16 production 4096 + anticipator", flush=True)
+    p = production
+    got_f, got_t, ant = p["got_f"], p["got_t"], p["ant"]
     assert np.isfinite(got_f).all()
-    assert np.array_equal(got_t, np.clip(np.rint(got_f), 0, cfg.d_max).astype(np.int32))
-    # anticipator: bit-exact given identical predicted token counts
+    assert np.array_equal(got_t, np.clip(np.rint(got_f), 0, p["model"].info.d_max).astype(np.int32))
     ref_load, ref_ovf, status, _ = oa.anticipate(got_t, ant.instance_id, ant.arrival_bucket, ant.rate,
                                                  ant.n_inst, ant.horizon)
-    got_load = load.cpu().numpy().reshape(ant.n_inst, ant.horizon)
-    assert status == 0 and np.array_equal(got_load, ref_load) and np.array_equal(ovf.cpu().numpy(), ref_ovf)
+    assert status == 0 and np.array_equal(p["load"], ref_load) and np.array_equal(p["ovf"], ref_ovf)
     per_inst = np.bincount(ant.instance_id, weights=got_t, minlength=ant.n_inst).astype(np.int64)
-    assert np.array_equal(got_load.sum(axis=1, dtype=np.int64) + ovf.cpu().numpy(), per_inst)
-    # predictor: sampled requests against the oracle
-    lengths = batch.valid_lengths()
-    pick = np.unique(np.concatenate([[0, n - 1, int(np.argmax(lengths)), int(np.argmin(lengths))],
-                                     np.random.default_rng(1).choice(n, 6, replace=False)]))
-    sub = wl.pack_prompts(lengths[pick], np.concatenate([batch.token_ids[batch.offsets[r]:batch.offsets[r + 1]] for r in pick]))
-    ref_f, ref_t = op.predict_load(ref, sub.token_ids, sub.offsets)
-    # the scale of the tolerance is the batch's RMS; the sample's RMS stands in for it
-    scale = np.maximum(np.abs(ref_f), np.sqrt(np.mean(ref_f ** 2)))
-    err = np.abs(got_f[pick] - ref_f) / scale
-    print(f"  sampled {len(pick)} requests (lengths {lengths[pick].tolist()}): max rel err {err.max():.3e}", flush=True)
-    assert err.max() < TOL_BF16
-    assert np.all(np.abs(got_t[pick] - ref_t) <= np.ceil(TOL_BF16 * scale) + 1)
+    assert np.array_equal(p["load"].sum(axis=1, dtype=np.int64) + p["ovf"], per_inst)
+
+
+def test_production_batch_chunks_bit_equal(production):
+    """All 4096 requests again in 16 calls of 256: the same bits as in the one call the benchmark times."""
+    print("predict bf16 production 4096: whole batch against chunks of 256", flush=True)
+    p = production
+    chunks_bit_equal(p["model"], p["batch"], p["got_f"], p["got_t"])
+
+
+def test_production_short_prompts_against_oracle(production):
+    """Every request of at most 48 tokens (366 of the 4096; short prompts carry the largest errors: few keys
+    to average the operands' rounding over) against the oracle."""
+    print("predict bf16 production 4096: every prompt of at most 48 tokens against the oracle", flush=True)
+    p = production
+    lengths = p["batch"].valid_lengths()
+    short = np.flatnonzero(lengths <= 48)
+    assert len(short) >= 300
+    check_against_pool("short prompts", p["path"], p["batch"], p["got_f"], p["got_t"], short, p["model"].info.d_max)
+
+
+def test_production_stratified_sample_against_oracle(production):
+    """72 longer requests spread evenly over the length ranks (49 to 2048 tokens, the longest included), the
+    first and the last request of the batch: each against the oracle."""
+    print("predict bf16 production 4096: length-stratified sample against the oracle", flush=True)
+    p = production
+    lengths = p["batch"].valid_lengths()
+    rest = stratified(lengths, np.flatnonzero(lengths > 48), 72)
+    picks = np.unique(np.concatenate([rest, [0, p["batch"].n_req - 1, int(np.argmax(lengths))]]))
+    picks = picks[lengths[picks] > 48]
+    check_against_pool("stratified", p["path"], p["batch"], p["got_f"], p["got_t"], picks, p["model"].info.d_max)
