@@ -72,32 +72,175 @@ def encoder_flops(cfg, lengths):
     return gemm, attn
 
 
-def time_cpu_oracle(model_path, batch, ant, budget_s=15.0):
-    """The fp64 oracle (predictor + anticipator) on the first requests of the batch, sized for
-    about `budget_s` seconds from a quick probe of this host's fp64 matmul rate."""
+def time_cpu_oracle(model_path, batch, ant, stream=None, budget_s=8.0):
+    """The fp64 oracle as it stands, on this machine's host cores, on bounded samples of the same workload:
+    the predictor + anticipator on the first requests of the batch, once on one core (numpy held to one
+    thread) and once over all cores this process may use (one single-threaded worker process per core, the
+    requests dealt among them); and the anticipator oracle alone (C, one core) on the whole record stream the
+    GPU leg times.  Samples are sized from a quick probe of this host's fp64 matmul rate."""
     from oracle import anticipator as oa
+    from oracle import pool as opool
     from oracle import predictor as op
+    try:
+        from threadpoolctl import threadpool_limits
+    except ImportError:                                   # without it numpy keeps its own thread count
+        threadpool_limits = None
     model = op.load_model(model_path)
-    a = np.random.default_rng(0).standard_normal((512, 1024))
-    b = np.random.default_rng(1).standard_normal((1024, 1024))
-    t0 = time.perf_counter()
-    for _ in range(3):
-        a @ b
-    rate = 3 * 2 * 512 * 1024 * 1024 / (time.perf_counter() - t0)          # flop/s
-    H, F, L = model["hidden"], model["ffn"], model["layers"]
     lengths = batch.valid_lengths()
+    H, F, L = model["hidden"], model["ffn"], model["layers"]
     per_req = L * (lengths * (8.0 * H * H + 4.0 * H * F) + 4.0 * H * lengths.astype(np.float64) ** 2)
-    n = int(np.searchsorted(np.cumsum(per_req), 0.25 * rate * budget_s)) + 1    # the oracle runs at about a quarter of the probe rate
-    n = max(1, min(n, batch.n_req))
-    offs = batch.offsets[: n + 1]
-    lens = None if batch.lengths is None else batch.lengths[:n]
+
+    def probe():
+        a = np.random.default_rng(0).standard_normal((512, 1024))
+        b = np.random.default_rng(1).standard_normal((1024, 1024))
+        a @ b
+        t0 = time.perf_counter()
+        for _ in range(3):
+            a @ b
+        return 3 * 2 * 512 * 1024 * 1024 / (time.perf_counter() - t0)          # flop/s
+
+    def sample_size(flops):
+        return max(1, min(int(np.searchsorted(np.cumsum(per_req), flops)) + 1, batch.n_req))
+
+    # one core
+    import contextlib
+    with (threadpool_limits(limits=1) if threadpool_limits else contextlib.nullcontext()):
+        rate1 = probe()
+        n1 = sample_size(0.5 * rate1 * budget_s)          # the oracle's mix of operations runs at about half the probe rate
+        offs = batch.offsets[: n1 + 1]
+        lens = None if batch.lengths is None else batch.lengths[:n1]
+        t0 = time.perf_counter()
+        _, tok = op.predict_load(model, batch.token_ids, offs, lens)
+        oa.anticipate(tok, ant.instance_id[:n1], ant.arrival_bucket[:n1], ant.rate, ant.n_inst, ant.horizon)
+        dt1 = time.perf_counter() - t0
+    threads1 = 1 if threadpool_limits else int(os.environ.get("OMP_NUM_THREADS", 0)) or (os.cpu_count() or 1)
+    single = {"value": n1 / dt1, "unit": "requests/s", "cores": threads1,
+              "sample": f"first {n1} requests ({int(lengths[:n1].sum())} tokens) of the batch, fp64 numpy + C, {dt1:.1f} s"}
+    # all cores: worker processes, each numpy single-threaded
+    cores = opool.workers_available(limit=64)
+    nc = sample_size(per_req[:n1].sum() / dt1 * budget_s * cores)
+    valid = batch.valid_lengths()
+    reqs = [batch.token_ids[batch.offsets[r]: batch.offsets[r] + valid[r]] for r in range(nc)]
     t0 = time.perf_counter()
-    _, tok = op.predict_load(model, batch.token_ids, offs, lens)
-    oa.anticipate(tok, ant.instance_id[:n], ant.arrival_bucket[:n], ant.rate, ant.n_inst, ant.horizon)
-    dt = time.perf_counter() - t0
-    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {"value": n / dt, "unit": "requests/s", "cores": threads, "kind": "oracle",
-            "sample": f"first {n} requests ({int(lengths[:n].sum())} tokens) of the batch, fp64 numpy + C, {dt:.1f} s"}
+    pred = opool.predict_requests(model_path, reqs, workers=cores)
+    tok = np.clip(np.rint(pred), 0, model["d_max"]).astype(np.int32)
+    oa.anticipate(tok, ant.instance_id[:nc], ant.arrival_bucket[:nc], ant.rate, ant.n_inst, ant.horizon)
+    dtc = time.perf_counter() - t0
+    out = {"value": nc / dtc, "unit": "requests/s", "cores": min(cores, nc), "kind": "oracle",
+           "sample": f"first {nc} requests ({int(lengths[:nc].sum())} tokens) of the batch dealt to {min(cores, nc)} "
+                     f"single-threaded worker processes (model read by each included), fp64 numpy + C, {dtc:.1f} s",
+           "host_cores": os.cpu_count(), "single_thread": single}
+    if stream is not None:
+        t0 = time.perf_counter()
+        oa.anticipate(stream.pred_tokens, stream.instance_id, stream.arrival_bucket, stream.rate, stream.n_inst,
+                      stream.horizon)
+        dts = time.perf_counter() - t0
+        n_s = int(stream.pred_tokens.shape[0])
+        out["anticipator"] = {"records_per_s": n_s / dts, "GB/s": (12.0 * n_s + 8.0 * stream.n_inst * stream.horizon) / dts / 1e9,
+                              "cores": 1, "sample": f"the whole {n_s}-record stream in arbitrary order, C oracle, {dts:.1f} s"}
+    return out
+
+
+def latency_leg(torch, ps, wl, dev, status, n_batches, warm, rate_per_s=2000.0, micro=8):
+    """The latency configuration: a seeded Poisson stream of requests at `rate_per_s` served in micro-batches of
+    `micro` by the 6-layer H768 encoder, ps_predict_load followed by ps_anticipate_static, replayed in real
+    time: batch b becomes ready when its last request has arrived, is launched then (or as soon as the batch
+    before it has finished), and its latency runs from ready to predictions and map complete on the device.
+    Two ways of issuing the same kernels: one launch after the other from the host ("eager"), and the whole call
+    captured once into a HIP graph on fixed staging buffers of the largest micro-batch, replayed per batch
+    after one device-to-device copy of the batch's inputs ("graph")."""
+    cfg = wl.MODELS["latency"].resolved()
+    tmp = tempfile.mkdtemp(prefix="ps_bench_lat_")
+    path = os.path.join(tmp, "latency.bin")
+    wl.write_model(path, cfg, wl.make_weights(cfg, seed=0))
+    model = ps.ps_model_load(path, 0)
+    os.remove(path)
+    os.rmdir(tmp)
+    total = warm + n_batches
+    n = total * micro
+    big = wl.make_prompts("latency", seed=0, n_req=n)
+    lengths = big.valid_lengths()
+    arrivals = wl.poisson_arrival_times(0, n, rate_per_s)
+    ready = arrivals[micro - 1:: micro]                                    # a batch closes with its last request
+    ant = wl.make_anticipator_inputs("small", seed=0, n=n, pred_tokens=np.zeros(n, np.int32))
+    bucket = np.minimum(np.floor(arrivals), ant.horizon - 1).astype(np.int32)
+    cap_tokens = micro * 512                                               # token slots of the largest micro-batch
+    # one staging row per batch: token ids | offsets (padded to 12) | instance | arrival bucket
+    row_w = cap_tokens + 12 + 2 * micro
+    rows = np.zeros((total, row_w), np.int32)
+    for b in range(total):
+        r0 = b * micro
+        t0, t1 = big.offsets[r0], big.offsets[r0 + micro]
+        rows[b, : t1 - t0] = big.token_ids[t0:t1]
+        rows[b, cap_tokens: cap_tokens + micro + 1] = big.offsets[r0: r0 + micro + 1] - t0
+        rows[b, cap_tokens + 12: cap_tokens + 12 + micro] = ant.instance_id[r0: r0 + micro]
+        rows[b, cap_tokens + 12 + micro:] = bucket[r0: r0 + micro]
+    rows_d = torch.from_numpy(rows).to(dev)
+    rate_d = torch.from_numpy(ant.rate).to(dev)
+    stage = torch.zeros(row_w, dtype=torch.int32, device=dev)
+    s_ids, s_offs = stage[:cap_tokens], stage[cap_tokens: cap_tokens + micro + 1]
+    s_inst, s_arr = stage[cap_tokens + 12: cap_tokens + 12 + micro], stage[cap_tokens + 12 + micro:]
+    pred_f = torch.empty(micro, dtype=torch.float32, device=dev)
+    pred_t = torch.empty(micro, dtype=torch.int32, device=dev)
+    load = torch.zeros(ant.n_inst * ant.horizon, dtype=torch.int32, device=dev)
+    ovf = torch.zeros(ant.n_inst, dtype=torch.int64, device=dev)
+    ws = ps.alloc_workspace(ps.ps_workspace_bytes(model, cap_tokens, micro), dev)
+
+    def call_on_stage():
+        ps.ps_predict_load(model, s_ids, s_offs, None, pred_f, pred_t, ws, status)
+        ps.ps_anticipate_static(pred_t, s_inst, s_arr, rate_d, ant.n_inst, ant.horizon, load, ovf, status)
+
+    def eager(b):
+        # the batch's own slices of the resident inputs; token slots = its real token count
+        row = rows_d[b]
+        n_tok = int(big.offsets[(b + 1) * micro] - big.offsets[b * micro])
+        ps.ps_predict_load(model, row[:n_tok], row[cap_tokens: cap_tokens + micro + 1], None, pred_f, pred_t, ws, status)
+        ps.ps_anticipate_static(pred_t, row[cap_tokens + 12: cap_tokens + 12 + micro], row[cap_tokens + 12 + micro:],
+                                rate_d, ant.n_inst, ant.horizon, load, ovf, status)
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        stage.copy_(rows_d[0])
+        for _ in range(3):
+            call_on_stage()                                                # first-call set-up happens outside the capture
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call_on_stage()
+
+    def replay(b):
+        stage.copy_(rows_d[b])
+        graph.replay()
+
+    def run(issue, sync):
+        lat, svc = np.zeros(total), np.zeros(total)
+        t_start = time.perf_counter() + 0.01 - ready[0]
+        for b in range(total):
+            while True:
+                now = time.perf_counter() - t_start
+                if now >= ready[b]:
+                    break
+            issue(b)
+            sync()
+            done = time.perf_counter() - t_start
+            lat[b], svc[b] = done - ready[b], done - now
+        t = slice(warm, total)
+        span = (ready[total - 1] + lat[total - 1]) - ready[warm]
+        return {"p50_ms": 1e3 * float(np.quantile(lat[t], 0.5)), "p99_ms": 1e3 * float(np.quantile(lat[t], 0.99)),
+                "mean_ms": 1e3 * float(lat[t].mean()), "service_p50_ms": 1e3 * float(np.quantile(svc[t], 0.5)),
+                "service_p99_ms": 1e3 * float(np.quantile(svc[t], 0.99)),
+                "requests_per_s": (n_batches - 1) * micro / span if n_batches > 1 else 0.0,
+                "capacity_requests_per_s": micro / float(svc[t].mean())}
+
+    out = {"workload": f"latency: 6-layer H768 A12 F3072 bf16 encoder, Poisson arrivals at {rate_per_s:.0f} requests/s in "
+                       f"micro-batches of {micro} (lognormal(5.0,0.9) lengths in [4,512]); anticipator 4 x 64",
+           "micro_batches": n_batches, "warmup_batches": warm, "tokens_per_batch_mean": float(lengths.sum()) / total,
+           "eager": run(eager, torch.cuda.synchronize)}
+    with torch.cuda.stream(side):
+        out["graph"] = run(replay, side.synchronize)
+    flags, _ = ps.ps_status_read(status)
+    out["status_flags"] = int(flags)
+    return out
 
 
 def main() -> int:
@@ -109,6 +252,8 @@ def main() -> int:
     ap.add_argument("--stream-records", type=int, default=44_100_000,
                     help="records of the anticipator bandwidth stream (0 = skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--latency-batches", type=int, default=2000,
+                    help="timed micro-batches of the latency leg, after a tenth as many warm-up ones (0 = skip)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run one plain elementwise copy of this many MiB (a known traffic for counter runs)")
     args = ap.parse_args()
@@ -237,9 +382,9 @@ def main() -> int:
     if args.stream_records > 0:
         del ws
         torch.cuda.empty_cache()
-        # two orders of the same record stream: as a request log (records in arrival order, which the
-        # library exploits) and shuffled (arrival buckets independent of position)
-        for key, kind in (("anticipator", "stream_by_arrival"), ("anticipator_any_order", "stream")):
+        # two orders of the same record stream: arrival buckets independent of position (the headline figure)
+        # and as a request log (the same records in arrival order, which the library exploits)
+        for key, kind in (("anticipator", "stream"), ("anticipator_by_arrival", "stream_by_arrival")):
             s_in = wl.make_anticipator_inputs(kind, seed=0, n=args.stream_records)
             sp, si, sa, sr = t32(s_in.pred_tokens), t32(s_in.instance_id), t32(s_in.arrival_bucket), t32(s_in.rate)
             sload = torch.zeros(s_in.n_inst * s_in.horizon, dtype=torch.int32, device=dev)
@@ -340,8 +485,13 @@ def main() -> int:
         fc_s = timed(lambda: ps.ps_forecast(fw, 64, fp, fd, 512, 24, fm, fo))
         out["forecaster"] = {"services": 512, "hidden": 64, "history": 24, "us_per_call": 1e6 * fc_s}
 
+    if args.latency_batches > 0:
+        torch.cuda.empty_cache()
+        out["latency"] = latency_leg(torch, ps, wl, dev, status, args.latency_batches, max(1, args.latency_batches // 10))
+
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = time_cpu_oracle(model_path, batch, ant)
+        stream = wl.make_anticipator_inputs("stream", seed=0, n=args.stream_records) if args.stream_records > 0 else None
+        out["cpu_baseline"] = time_cpu_oracle(model_path, batch, ant, stream)
     try:
         os.remove(model_path)
         os.rmdir(tmp)

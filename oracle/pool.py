@@ -1,11 +1,13 @@
 """Runs the fp64 predictor oracle over many requests on several host cores.
 
+TEST INFRASTRUCTURE ONLY, like the rest of this package: only tests and the benchmark's CPU-baseline leg use it.
+
 A request's prediction depends on nothing but its own tokens, so the requests are dealt to worker
 processes (this file run as a program), each with its own copy of the model read from the model
 file.  The workers import only the oracle and numpy and run single-threaded; the process that
 starts them may hold a GPU context, they never touch it.
 
-    python -m tests.oracle_pool <model file> <requests .npz> <output .npy>
+    python -m oracle.pool <model file> <requests .npz> <output .npy>
 """
 from __future__ import annotations
 
@@ -52,7 +54,7 @@ def predict_requests(model_path: str, requests: Sequence[np.ndarray], workers: i
             lens = np.array([len(requests[i]) for i in share[w]], np.int64)
             ids = np.concatenate([np.asarray(requests[i], np.int64) for i in share[w]]) if share[w] else np.zeros(0, np.int64)
             np.savez(src, lengths=lens, ids=ids)
-            procs.append((subprocess.Popen([sys.executable, "-m", "tests.oracle_pool", model_path, src, dst],
+            procs.append((subprocess.Popen([sys.executable, "-m", "oracle.pool", model_path, src, dst],
                                            cwd=ROOT, env=env), dst))
         try:
             for w, (p, dst) in enumerate(procs):

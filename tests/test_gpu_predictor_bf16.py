@@ -9,7 +9,7 @@ import pytest
 from oracle import predictor as op
 from paper_2504_03702_amd import binding as ps
 from paper_2504_03702_amd import workloads as wl
-from tests import oracle_pool
+from oracle import pool as oracle_pool
 from tests.gpu_util import TOL_BF16, rel_err, run_predict
 
 pytestmark = pytest.mark.gpu
