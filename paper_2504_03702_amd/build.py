@@ -13,7 +13,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpreserve.so")
 
-SOURCES = ["api.hip", "rowops.hip", "encoder_f32.hip", "encoder_bf16.hip", "gemm_bf16.hip", "attention_bf16.hip",
+SOURCES = ["api.hip", "rowops.hip", "encoder_f32.hip", "encoder_bf16.hip", "gemm_bf16.hip", "skinny_gemm.hip", "attention_bf16.hip",
            "anticipate.hip", "lookahead.hip", "scaler.hip", "router.hip", "forecaster.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -47,6 +47,26 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+// erf-GELU x * Phi(x) with Phi(x) - 1/2 = x * Q((x / 4.5)^2) on |x| <= 4.5 (Q: degree-8 least-squares
+// fit on Chebyshev nodes) and Phi clamped beyond; absolute error of the result below 6e-5, under the
+// bf16 rounding of the stored value wherever the value is not itself tiny.  A dozen full-rate
+// operations instead of the several dozen of a branching erff.
+__device__ __forceinline__ float gelu_erf(float v) {
+    const float xc = fminf(fmaxf(v, -4.5f), 4.5f);
+    const float u = xc * (1.0f / 4.5f);
+    const float t = u * u;
+    float q = 8.248823390e-01f;
+    q = fmaf(q, t, -4.479837417e+00f);
+    q = fmaf(q, t, 1.069920200e+01f);
+    q = fmaf(q, t, -1.489329668e+01f);
+    q = fmaf(q, t, 1.354238783e+01f);
+    q = fmaf(q, t, -8.567420454e+00f);
+    q = fmaf(q, t, 3.921988782e+00f);
+    q = fmaf(q, t, -1.335489713e+00f);
+    q = fmaf(q, t, 3.986949891e-01f);
+    return v * fmaf(xc, q, 0.5f);
+}
+
 // Record a fault found in device data: OR the flag, keep the smallest index.  first_bad holds
 // (2^62 - index) so that a maximum over a zero-initialised word finds the smallest index.
 // Faults are exceptional, so the two atomics are off the fast path.

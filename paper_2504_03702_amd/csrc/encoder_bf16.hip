@@ -54,6 +54,15 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
     // the stream entering layer 0 is the embedding LayerNorm of the sums the embed kernel left in (x, la)
     const float *sg = m->lne_g, *sbeta = m->lne_b;
 #define PS_TIMED(FAM, CALL) do { ProfScope p_(m, FAM, s); CALL; } while (0)
+    // the per-request side maps: the tiled kernel, or for calls of a few requests the streaming one
+    const bool skinny = n_req <= PS_SKINNY_ROWS;
+    // (K = the map's contraction length; the hi | lo forms hold 2 K columns per row of A and of the repeated W)
+    auto side_gemm = [&](GemmEpilogue epi, const bf16_t* A, const void* W, const float* bias, const ResidualSrc& r, void* C,
+                         int N, int K) {
+        const int k_cols = epi == EPI_Q_MAPPED ? K : 2 * K;
+        if (skinny) launch_skinny_gemm_bf16(epi, A, (const bf16_t*)W, bias, r, C, N, K, H, n_req_dev, s);
+        else launch_gemm_bf16(epi, A, (const bf16_t*)W, bias, r, C, nullptr, ws.cls_rows, N, k_cols, H, n_req_dev, nullptr, s);
+    };
     for (int l = 0; l < f.layers; ++l) {
         const LayerWeights& w = m->layers[(size_t)l];
         // After the last layer only the first row of every request goes on (to the head), and within
@@ -81,8 +90,7 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
                                                    qk, vt, ws.max_rows, 2 * H, H, H, qkv_rows, clk, s));
             const ResidualSrc first_rows = {nullptr, nullptr, ws.sa, nullptr, nullptr, ws.row_start, ws.seq_len, nullptr, nullptr, w.c_qkv};
             PS_TIMED(PS_FAM_REFINE, launch_cls_rows(m, n_req, ws, x, (bf16_t*)ws.cls_a, s));
-            PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_Q_MAPPED, (const bf16_t*)ws.cls_a, (const bf16_t*)w.w_qkv, w.b_qkv,
-                                                     first_rows, qk, nullptr, ws.cls_rows, H, H, H, n_req_dev, nullptr, s));
+            PS_TIMED(PS_FAM_REFINE, side_gemm(EPI_Q_MAPPED, (const bf16_t*)ws.cls_a, w.w_qkv, w.b_qkv, first_rows, qk, H, H));
         }
         PS_TIMED(PS_FAM_ATTENTION, launch_attention_bf16(m, n_req, ws, last, s));
         if (!last)
@@ -91,8 +99,7 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
         // output projection again for each request's first row from the hi | lo pairs the attention
         // kernel left in cls_a (see the feed-forward refinement below)
         const ResidualSrc in_cls = {x, ws.la, ws.sa, sg, sbeta, ws.row_start, ws.seq_len, x1, ps, nullptr};
-        PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_RESIDUAL_MAPPED, (const bf16_t*)ws.cls_a, (const bf16_t*)w.w_od,
-                                                 w.b_o, in_cls, ws.lb, nullptr, ws.cls_rows, H, 2 * H, H, n_req_dev, nullptr, s));
+        PS_TIMED(PS_FAM_REFINE, side_gemm(EPI_RESIDUAL_MAPPED, (const bf16_t*)ws.cls_a, w.w_od, w.b_o, in_cls, ws.lb, H, H));
         if (!last) {
             PS_TIMED(PS_FAM_LAYERNORM, launch_ln_stats(ws.ps, ws.sb, m->ln_eps, H, ws.max_rows, rows, s));
             PS_TIMED(PS_FAM_GEMM, launch_gemm_bf16(EPI_BIAS_GELU, x1, (const bf16_t*)w.w_1, w.d_1, fold_1, g, nullptr,
@@ -107,10 +114,8 @@ void run_encoder_bf16(const ps_model* m, int32_t n_req, const Workspace& ws, hip
         // weights repeated): bf16 rounding of these two tensors is the dominant error of the prediction
         // and acts row by row, so the pass removes it where it matters at < 1 % of the block's cost.
         PS_TIMED(PS_FAM_REFINE, launch_cls_gather(m, n_req, ws, x1, ws.lb, ws.sb, w.ln1_g, w.ln1_b, s));
-        PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_GELU_SPLIT, (const bf16_t*)ws.cls_a, (const bf16_t*)w.w_1d, w.b_1,
-                                                 none, ws.cls_g, nullptr, ws.cls_rows, F, 2 * H, H, n_req_dev, nullptr, s));
-        PS_TIMED(PS_FAM_REFINE, launch_gemm_bf16(EPI_RESIDUAL_MAPPED, (const bf16_t*)ws.cls_g, (const bf16_t*)w.w_2d,
-                                                 w.b_2, mid_cls, ws.la, nullptr, ws.cls_rows, H, 2 * F, H, n_req_dev, nullptr, s));
+        PS_TIMED(PS_FAM_REFINE, side_gemm(EPI_GELU_SPLIT, (const bf16_t*)ws.cls_a, w.w_1d, w.b_1, none, ws.cls_g, F, H));
+        PS_TIMED(PS_FAM_REFINE, side_gemm(EPI_RESIDUAL_MAPPED, (const bf16_t*)ws.cls_g, w.w_2d, w.b_2, mid_cls, ws.la, H, F));
         if (!last)
             PS_TIMED(PS_FAM_LAYERNORM, launch_ln_stats(ws.ps, ws.sa, m->ln_eps, H, ws.max_rows, rows, s));
         else

@@ -39,26 +39,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 #define GLOBAL_AS __attribute__((address_space(1)))
 #define LDS_AS __attribute__((address_space(3)))
 
-// erf-GELU x * Phi(x) with Phi(x) - 1/2 = x * Q((x / 4.5)^2) on |x| <= 4.5 (Q: degree-8 least-squares
-// fit on Chebyshev nodes) and Phi clamped beyond; absolute error of the result below 6e-5, under the
-// bf16 rounding of the stored value wherever the value is not itself tiny.  A dozen full-rate
-// operations instead of the several dozen of a branching erff.
-__device__ __forceinline__ float gelu_erf(float v) {
-    const float xc = fminf(fmaxf(v, -4.5f), 4.5f);
-    const float u = xc * (1.0f / 4.5f);
-    const float t = u * u;
-    float q = 8.248823390e-01f;
-    q = fmaf(q, t, -4.479837417e+00f);
-    q = fmaf(q, t, 1.069920200e+01f);
-    q = fmaf(q, t, -1.489329668e+01f);
-    q = fmaf(q, t, 1.354238783e+01f);
-    q = fmaf(q, t, -8.567420454e+00f);
-    q = fmaf(q, t, 3.921988782e+00f);
-    q = fmaf(q, t, -1.335489713e+00f);
-    q = fmaf(q, t, 3.986949891e-01f);
-    return v * fmaf(xc, q, 0.5f);
-}
-
 // Sum over 8 consecutive lanes (lanes 8 r .. 8 r + 7) with DPP moves; every one of them gets the total.
 // The order of the additions is fixed, so the result does not change from run to run.
 template <int CTRL>
@@ -89,7 +69,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(
     int N, int K, int hidden, const int32_t* __restrict__ total_rows, int64_t* __restrict__ clk) {
     using T = Tile<BM, BN, WM, WN>;
     constexpr int STAGE = T::A_BYTES + T::B_BYTES;      // an A slice followed by a W slice
-    constexpr int EPI_BYTES = 32768 / T::NW;            // per-wavefront transpose region of the epilogue
+    constexpr int EPI_BYTES = 4096;                     // per-wavefront transpose region of the epilogue
     static_assert(2 * STAGE + T::NW * EPI_BYTES <= 160 * 1024, "LDS budget");
     __shared__ __align__(1024) unsigned char smem[2 * STAGE + T::NW * EPI_BYTES];
 
@@ -551,9 +531,11 @@ template <int BM, int BN, int WM, int WN>
 void launch_cfg(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias, ResidualSrc residual,
                 void* C, bf16_t* vt, int64_t max_rows, int N, int K, int hidden, const int32_t* total_rows,
                 int64_t* clk, hipStream_t s) {
-    // persistent: one workgroup per compute unit (fewer if there cannot be that many tiles)
+    // persistent: one workgroup per compute unit (fewer if there cannot be that many tiles); the small tiles
+    // leave room for two workgroups per unit (LDS and registers), which then hide each other's waits
     const int64_t tiles = (max_rows + BM - 1) / BM * (N / BN);
-    const int64_t wgs = tiles < 256 ? (tiles + 7) / 8 * 8 : 256;
+    const int64_t most = BM * BN <= 128 * 128 ? 512 : 256;
+    const int64_t wgs = tiles < most ? (tiles + 7) / 8 * 8 : most;
     const dim3 grid((unsigned)wgs), block(WM * WN * 64);
 #define PS_LAUNCH(E)                                                                                       \
     hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, E>), grid, block, 0, s, A, W, bias, residual, C, vt, \
@@ -578,10 +560,11 @@ void launch_cfg(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float*
 void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias,
                       ResidualSrc residual, void* C, bf16_t* vt, int64_t max_rows, int N, int K,
                       int hidden, const int32_t* total_rows, int64_t* clk, hipStream_t s) {
-    // The per-request side problems that reduce to `hidden` columns have few tiles (one row per request,
-    // few tile columns) and long contractions: 128 x 128 tiles give four times as many workgroups to
-    // spread them over.
-    if (epi == EPI_RESIDUAL_MAPPED || epi == EPI_Q_MAPPED)
+    // Problems with few 256 x 256 tiles (the per-request side problems: one row per request; whole calls on a
+    // micro-batch of a few requests) would leave most compute units idle: 128 x 128 tiles give four times as
+    // many workgroups to spread them over.
+    const int64_t big_tiles = (max_rows + 255) / 256 * (N / 256);
+    if (epi == EPI_RESIDUAL_MAPPED || epi == EPI_Q_MAPPED || big_tiles < 128)
         launch_cfg<128, 128, 2, 2>(epi, A, W, bias, residual, C, vt, max_rows, N, K, hidden, total_rows, clk, s);
     else
         launch_cfg<256, 256, 2, 4>(epi, A, W, bias, residual, C, vt, max_rows, N, K, hidden, total_rows, clk, s);

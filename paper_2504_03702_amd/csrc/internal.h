@@ -133,6 +133,11 @@ struct ResidualSrc {
 void launch_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias,
                       ResidualSrc res, void* C, bf16_t* vt, int64_t max_rows, int N, int K,
                       int hidden, const int32_t* total_rows, int64_t* clk, hipStream_t s);
+// The per-request forms (EPI_GELU_SPLIT, EPI_RESIDUAL_MAPPED, EPI_Q_MAPPED) for calls of at most PS_SKINNY_ROWS
+// requests: a stream over W with the contraction split among a workgroup's wavefronts.
+#define PS_SKINNY_ROWS 16
+void launch_skinny_gemm_bf16(GemmEpilogue epi, const bf16_t* A, const bf16_t* W, const float* bias, ResidualSrc residual,
+                             void* C, int N, int K, int hidden, const int32_t* n_rows, hipStream_t s);
 void launch_cls_gather(const ps_model* m, int32_t n_req, const Workspace& ws, const bf16_t* y_hi, const bf16_t* y_lo,
                        const float2* stats, const float* gamma, const float* beta, hipStream_t s);
 // out[r][0:hidden] = x[first row of request r] for every request (zeros for faulty ones and padding rows).

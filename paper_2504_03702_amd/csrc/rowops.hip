@@ -234,14 +234,18 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------
-// head: one workgroup per request.  c = final state of the request's first row (bf16 path: the
-// last LayerNorm recomputed in fp32 from the row's sums and statistics); every wavefront
-// takes hidden units j = wave, wave + 4, ...: a 64-lane dot product of c with row j of W_h1^T
-// reduced across the wavefront, ReLU, times w_h2[j]; the four partial sums are added in a fixed
-// order.  pred_tokens = clamp(rint(y), 0, d_max) with rint rounding half to even.
+// head: one workgroup of 16 wavefronts per request.  c = final state of the request's first row
+// (bf16 path: the last LayerNorm recomputed in fp32 from the row's sums and statistics); wavefront w
+// takes hidden units j = w, w + 16, ..., four of them at a time (their loads are all requested before
+// the first is used: with few requests the kernel's time is the latency of these loads): 64-lane dot
+// products of c with rows of W_h1^T reduced across the wavefront, ReLU, times w_h2[j]; the sixteen
+// partial sums are added in a fixed order.  pred_tokens = clamp(rint(y), 0, d_max) with rint
+// rounding half to even.
 // ------------------------------------------------------------------------------------------
+const int kHeadWaves = 16;
+
 template <typename T>
-__global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, const int32_t* __restrict__ seq_len,
+__global__ __launch_bounds__(kHeadWaves * 64) void head_kernel(const T* __restrict__ x, const int32_t* __restrict__ seq_len,
                                                    const int32_t* __restrict__ row_start,
                                                    const int32_t* __restrict__ bad_req,
                                                    const bf16_t* __restrict__ y_lo, const float2* __restrict__ stats,
@@ -251,7 +255,7 @@ __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, cons
                                                    const float* __restrict__ w_h2, float b_h2, int d_max,
                                                    float* __restrict__ pred_f, int32_t* __restrict__ pred_tokens,
                                                    ps_status* st) {
-    extern __shared__ float s_c[];           // [H] + 4 partial sums
+    extern __shared__ float s_c[];           // [H] + kHeadWaves partial sums
     const int r = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (seq_len[r] <= 0 || bad_req[r]) {
@@ -267,25 +271,66 @@ __global__ __launch_bounds__(256) void head_kernel(const T* __restrict__ x, cons
         const float2 st2 = stats[crow];
         const bf16_t* hi = (const bf16_t*)x + crow * H;
         const bf16_t* lo = y_lo + crow * H;
-        for (int i = threadIdx.x; i < H; i += 256)
+        for (int i = threadIdx.x; i < H; i += kHeadWaves * 64)
             s_c[i] = ((bf16_to_f32(hi[i]) + bf16_to_f32(lo[i])) - st2.x) * st2.y * ln_g[i] + ln_b[i];
     } else {
         const T* c = x + crow * H;
-        for (int i = threadIdx.x; i < H; i += 256) s_c[i] = load_elem<T>(c, i);
+        for (int i = threadIdx.x; i < H; i += kHeadWaves * 64) s_c[i] = load_elem<T>(c, i);
     }
     __syncthreads();
     float acc = 0.f;
-    for (int j = wave; j < Hh; j += 4) {
-        const float* w = w_h1t + (int64_t)j * H;
-        float dot = 0.f;
-        for (int i = lane; i < H; i += 64) dot += s_c[i] * w[i];
-        dot = wave_sum(dot) + b_h1[j];
-        acc += (dot < 0.f ? 0.f : dot) * w_h2[j];   // ReLU that lets a NaN through to the check below
+    const bool wide = (H & 255) == 0 && H <= 2048;       // rows of whole 16-byte pieces per lane (all bf16 models)
+    for (int j0 = wave; j0 < Hh; j0 += 4 * kHeadWaves) {
+        float dot[4] = {0.f, 0.f, 0.f, 0.f};
+        if (wide) {
+            // lane l holds the 4-element pieces l, l + 64, ... of a row; the loads of four units' rows are all
+            // requested before the first product is taken, four pieces (1024 elements) at a time
+            const int nch = H >> 8;
+            for (int c0 = 0; c0 < nch; c0 += 4) {
+                float4 wv[4][4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int j = min(j0 + u * kHeadWaves, Hh - 1);      // (a unit past the end re-reads the last row)
+                    const float4* w = (const float4*)(w_h1t + (int64_t)j * H);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        wv[u][c] = c0 + c < nch ? w[lane + 64 * (c0 + c)] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    if (c0 + c < nch) {
+                        const float4 cv = ((const float4*)s_c)[lane + 64 * (c0 + c)];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            dot[u] = fmaf(cv.x, wv[u][c].x, fmaf(cv.y, wv[u][c].y, fmaf(cv.z, wv[u][c].z, fmaf(cv.w, wv[u][c].w, dot[u]))));
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = j0 + u * kHeadWaves;
+                if (j < Hh) {
+                    const float* w = w_h1t + (int64_t)j * H;
+                    for (int i = lane; i < H; i += 64) dot[u] = fmaf(s_c[i], w[i], dot[u]);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int j = j0 + u * kHeadWaves;
+            if (j < Hh) {
+                const float d = wave_sum(dot[u]) + b_h1[j];
+                acc += (d < 0.f ? 0.f : d) * w_h2[j];   // ReLU that lets a NaN through to the check below
+            }
+        }
     }
     if (lane == 0) s_c[H + wave] = acc;
     __syncthreads();
     if (threadIdx.x == 0) {
-        const float y = ((s_c[H] + s_c[H + 1]) + (s_c[H + 2] + s_c[H + 3])) + b_h2;
+        float y = 0.f;
+        for (int w = 0; w < kHeadWaves; ++w) y += s_c[H + w];
+        y += b_h2;
         pred_f[r] = y;
         if (y != y) {
             pred_tokens[r] = -1;
@@ -404,14 +449,14 @@ void launch_embed(const ps_model* m, const int32_t* token_ids, const int32_t* of
 void launch_head(const ps_model* m, int32_t n_req, const Workspace& ws, float* pred_f, int32_t* pred_tokens,
                  ps_status* st, hipStream_t s) {
     const ps_model_info& f = m->info;
-    const size_t lds = sizeof(float) * (size_t)(f.hidden + 4);
+    const size_t lds = sizeof(float) * (size_t)(f.hidden + kHeadWaves);
     if (f.dtype == 1)
-        hipLaunchKernelGGL(head_kernel<bf16_t>, dim3(n_req), dim3(256), lds, s, (const bf16_t*)ws.x,
+        hipLaunchKernelGGL(head_kernel<bf16_t>, dim3(n_req), dim3(kHeadWaves * 64), lds, s, (const bf16_t*)ws.x,
                            ws.seq_len, ws.row_start, ws.bad_req, (const bf16_t*)ws.la, (const float2*)ws.sa,
                            (const float*)m->layers.back().ln2_g, (const float*)m->layers.back().ln2_b, f.hidden, f.head_hidden, m->w_h1t, m->b_h1, m->w_h2,
                            m->b_h2, f.d_max, pred_f, pred_tokens, st);
     else
-        hipLaunchKernelGGL(head_kernel<float>, dim3(n_req), dim3(256), lds, s, (const float*)ws.x,
+        hipLaunchKernelGGL(head_kernel<float>, dim3(n_req), dim3(kHeadWaves * 64), lds, s, (const float*)ws.x,
                            ws.seq_len, ws.row_start, ws.bad_req, (const bf16_t*)nullptr, (const float2*)nullptr,
                            (const float*)nullptr, (const float*)nullptr, f.hidden, f.head_hidden, m->w_h1t, m->b_h1, m->w_h2,
                            m->b_h2, f.d_max, pred_f, pred_tokens, st);
