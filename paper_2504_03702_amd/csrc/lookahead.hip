@@ -8,9 +8,12 @@
 // constant over the record's slots [lo, hi) = [s + i_begin, s + i_end).  So with two difference
 // arrays, dA[lo] += sign (P - s), dA[hi] -= sign (P - s) and dB[lo] += sign, dB[hi] -= sign,
 // the map is N[t] = prefix(dA)[t] + t * prefix(dB)[t].  Both differences of a slot travel in one
-// 64-bit word, offset * 2^24 + slope (sums of signed numbers add component-wise as long as the slope
-// part stays below 2^23 in magnitude, i.e. fewer than 8 million records start or end in one slot), so a
-// record costs two 64-bit integer atomic adds whatever its length.  Updates at or beyond map_len
+// 64-bit word, offset * 2^24 + slope, so a record costs two 64-bit integer atomic adds whatever its
+// length.  Sums of signed numbers add component-wise as long as the slope part stays below 2^23 and the
+// offset part below 2^39 in magnitude.  Nothing is assumed about where records fall (the paper admits
+// every request at the map's origin, so all of them may start in one slot): a call is folded in parts
+// of at most 2^22 records, each cleared, scattered and scanned into the caller's map on its own; with
+// |offset| = |P - s| < 2^17 per record neither part of any word can leave its field.  Updates at or beyond map_len
 // never reach a slot inside the map and are dropped; the tokens of iterations beyond the map go to
 // overflow[] in closed form.  Rows here are long (thousands of iterations), so the differences live in
 // an L2-resident global array rather than in LDS.  Kernels: clear the differences; one thread per
@@ -30,14 +33,14 @@ __global__ __launch_bounds__(256) void lookahead_clear_kernel(ulonglong2* __rest
 __global__ __launch_bounds__(256) void lookahead_scatter_kernel(
     const int32_t* __restrict__ instance_id, const int32_t* __restrict__ start_iter,
     const int32_t* __restrict__ prompt_tokens, const int32_t* __restrict__ i_begin,
-    const int32_t* __restrict__ i_end, const int32_t* __restrict__ sign, int64_t n, int n_inst, int map_len,
-    unsigned long long* __restrict__ d2, int64_t* __restrict__ overflow, ps_status* st) {
+    const int32_t* __restrict__ i_end, const int32_t* __restrict__ sign, int64_t n, int64_t first_index, int n_inst,
+    int map_len, unsigned long long* __restrict__ d2, int64_t* __restrict__ overflow, ps_status* st) {
     for (int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x; r < n; r += (int64_t)gridDim.x * 256) {
         const int k = instance_id[r], s = start_iter[r], P = prompt_tokens[r];
         const int b = i_begin[r], e = i_end[r], sg = sign[r];
-        if ((unsigned)k >= (unsigned)n_inst || (unsigned)s >= (unsigned)map_len || (unsigned)P >= (1u << 20) || b < 0 ||
+        if ((unsigned)k >= (unsigned)n_inst || (unsigned)s >= (unsigned)map_len || (unsigned)P >= (unsigned)PS_MAX_PROMPT || b < 0 ||
             e < b || e > PS_MAX_ITER || (sg != 1 && sg != -1)) {
-            report_fault(st, PS_ST_BAD_RECORD, r);
+            report_fault(st, PS_ST_BAD_RECORD, first_index + r);
             continue;
         }
         if (b == e) continue;
@@ -131,15 +134,23 @@ extern "C" int ps_lookahead_update(const int32_t* instance_id, const int32_t* st
     (void)hipGetLastError();
     const int64_t n16 = (int64_t)(need / 16);
     const unsigned clear_blocks = (unsigned)((n16 + 255) / 256 < 2048 ? (n16 + 255) / 256 : 2048);
-    hipLaunchKernelGGL(lookahead_clear_kernel, dim3(clear_blocks), dim3(256), 0, s, (ulonglong2*)workspace, n16);
-    if (n_rec > 0) {
-        const int64_t want = (n_rec + 255) / 256;
-        const unsigned blocks = (unsigned)(want < 8192 ? want : 8192);
-        hipLaunchKernelGGL(lookahead_scatter_kernel, dim3(blocks), dim3(256), 0, s, instance_id, start_iter,
-                           prompt_tokens, i_begin, i_end, sign, n_rec, n_inst, map_len,
-                           (unsigned long long*)workspace, overflow, status);
+    // parts of at most kPart records: the packed differences of one slot cannot overflow their fields within a
+    // part (see the top of this file); the map accumulates, so the parts add up to the whole
+    const int64_t kPart = (int64_t)1 << 22;
+    for (int64_t at = 0; at < n_rec || at == 0; at += kPart) {
+        const int64_t n_part = n_rec - at < kPart ? n_rec - at : kPart;
+        const bool last = at + kPart >= n_rec;
+        hipLaunchKernelGGL(lookahead_clear_kernel, dim3(clear_blocks), dim3(256), 0, s, (ulonglong2*)workspace, n16);
+        if (n_part > 0) {
+            const int64_t want = (n_part + 255) / 256;
+            const unsigned blocks = (unsigned)(want < 8192 ? want : 8192);
+            hipLaunchKernelGGL(lookahead_scatter_kernel, dim3(blocks), dim3(256), 0, s, instance_id + at, start_iter + at,
+                               prompt_tokens + at, i_begin + at, i_end + at, sign + at, n_part, at, n_inst, map_len,
+                               (unsigned long long*)workspace, overflow, status);
+        }
+        // the fractions are written once, from the finished map
+        hipLaunchKernelGGL(lookahead_scan_kernel, dim3((unsigned)n_inst), dim3(256), 0, s, (const long long*)workspace,
+                           n_inst, map_len, kv_tokens, capacity, last ? fraction : nullptr, status);
     }
-    hipLaunchKernelGGL(lookahead_scan_kernel, dim3((unsigned)n_inst), dim3(256), 0, s, (const long long*)workspace,
-                       n_inst, map_len, kv_tokens, capacity, fraction, status);
     return hipGetLastError() == hipSuccess ? PS_OK : PS_EHIP;
 }

@@ -6,7 +6,7 @@ imported by the tests and the benchmark to feed both the GPU library and the CPU
 oracle with the same bytes.  It imports neither of them.
 
 Shapes follow the paper's workload description (Sec. 2.2 "Challenge 2": prompt
-lengths 7..911 tokens, median 52; responses 5..632, median 87; Sec. 3.3.1: response
+lengths 7..911 tokens, median 52; responses 5..632, median 87; Sec. 3.4.1: response
 lengths up to 4096).  Prompt contents and traces themselves are not available, so
 token ids, lengths, arrivals and instance assignments are drawn from the stated
 distributions with ``numpy.random.default_rng(seed)`` in a fixed order.
@@ -54,7 +54,7 @@ class ModelConfig:
     n_soft: int = 0
     head_hidden: int = 0          # 0 -> same as hidden
     dtype: int = DTYPE_BF16
-    d_max: int = 4096             # longest response the paper considers (Sec. 3.3.1, Table 2)
+    d_max: int = 4096             # longest response the paper considers (Sec. 3.4.1, Table 2)
     ln_eps: float = 1e-12
 
     def resolved(self) -> "ModelConfig":

@@ -161,3 +161,26 @@ def test_scaler_boundaries_and_scale_down():
     got = run_scaler(calm, [1000, 2000, 500, 400], 64)
     assert got[3] == 0 and got[4] == 1
     assert abs(got[5] - (4 - (0.299 + 0.05 + 0.298 + 0.025) / 0.3)) < 1e-12
+
+
+def test_all_requests_admitted_at_the_maps_origin():
+    """The paper's own use: every request enters its instance's map at the origin once its prefill is done, so
+    all records of a rebuild start in slot 0.  Nine million of them on one instance (more than one packed
+    difference word could count at once: the call is folded in parts), with cancelling removals mixed in;
+    a second, small instance beside it.  Bit-exact against the oracle."""
+    print("lookahead 9 M records at slot 0", flush=True)
+    n = 9_000_000
+    rng = np.random.default_rng(21)
+    inst = np.zeros(n, np.int32)
+    inst[rng.integers(0, n, 1000)] = 1
+    start = np.zeros(n, np.int32)
+    prompt = rng.integers(1, 200, n).astype(np.int32)
+    prompt[:: 1_000_003] = 131071                           # the largest prompt length accepted
+    i_begin = np.zeros(n, np.int32)
+    i_end = rng.integers(1, 5, n).astype(np.int32)
+    sign = np.where(rng.random(n) < 0.45, -1, 1).astype(np.int32)
+    cols = [inst, start, prompt, i_begin, i_end, sign]
+    (kv, ovf, _, flags, _), (rkv, rovf, rst, _) = both(cols, 2, 8)
+    assert rst == 0
+    assert (flags & ~ps.PS_ST_RANGE) == 0                   # (an intermediate part may leave the int32 range and return)
+    assert np.array_equal(kv, rkv) and np.array_equal(ovf, rovf)
