@@ -312,7 +312,7 @@ def main() -> int:
     la_inst = inst % la.n_inst
     la_kv = torch.zeros(la.n_inst * la.map_len, dtype=torch.int32, device=dev)
     la_ovf = torch.zeros(la.n_inst, dtype=torch.int64, device=dev)
-    la_ws = ps.alloc_workspace(ps.ps_lookahead_workspace_bytes(la.n_inst, la.map_len), dev)
+    la_ws = ps.alloc_workspace(ps.ps_lookahead_workspace_bytes(n_req, la.n_inst, la.map_len), dev)
 
     def step():
         ps.ps_predict_load(model, ids, offs, lens, pred_f, pred_t, ws, status)
@@ -417,7 +417,7 @@ def main() -> int:
         n_rec = cols[0].numel()
         kv = torch.zeros(s_la.n_inst * s_la.map_len, dtype=torch.int32, device=dev)
         ovf2 = torch.zeros(s_la.n_inst, dtype=torch.int64, device=dev)
-        lws = ps.alloc_workspace(ps.ps_lookahead_workspace_bytes(s_la.n_inst, s_la.map_len), dev)
+        lws = ps.alloc_workspace(ps.ps_lookahead_workspace_bytes(n_rec, s_la.n_inst, s_la.map_len), dev)
         reps = 10
         for _ in range(2):
             ps.ps_lookahead_update(*cols, s_la.n_inst, s_la.map_len, kv, ovf2, lws, status=status)

@@ -181,20 +181,21 @@ int ps_anticipate_static(const int32_t* pred_tokens, const int32_t* instance_id,
  *   capacity   [n_inst] int32 token capacities M, needed only with `fraction`
  *   fraction   [n_inst * map_len] float or NULL, out: kv_tokens / capacity after the update (NaN for
  *              an instance whose capacity is < 1)
- *   workspace  device scratch of at least ps_lookahead_workspace_bytes(n_inst, map_len) bytes,
+ *   workspace  device scratch of at least ps_lookahead_workspace_bytes(n_rec, n_inst, map_len) bytes,
  *              256-byte aligned; contents undefined before and after
  *   status     device ps_status or NULL.  A record with instance outside [0, n_inst), start_iter
  *              outside [0, map_len), prompt_tokens outside [0, PS_MAX_PROMPT), i_begin < 0, i_end < i_begin,
  *              i_end > PS_MAX_ITER or sign not +1 / -1 is skipped (PS_ST_BAD_RECORD); a slot that
  *              leaves the int32 range keeps its low 32 bits (PS_ST_RANGE).
  * Integer arithmetic throughout: the result does not depend on record order and is bit-exact, however many
- * records start or end in one slot (a call is folded in parts of 2^22 records, within which no intermediate
- * sum can leave its field).
+ * records start or end in one slot (lists of 65536 records or more over maps of at most 12800 slots and 4096
+ * instances are binned by instance and folded in LDS with wide counters; other calls use packed global counters
+ * and are folded in parts of 2^22 records, within which no intermediate sum can leave its field).
  * n_rec == 0 is allowed (with `fraction` it recomputes the fractions of the map as it stands).
  * Errors: PS_EINVAL, PS_EWORKSPACE, PS_EUNSUPPORTED (map_len above PS_MAX_ITER + 1), PS_EHIP. */
 #define PS_MAX_ITER  65535       /* largest i_end ps_lookahead_update accepts                 */
 #define PS_MAX_PROMPT 131072     /* prompt_tokens must be below this (2^17)                   */
-size_t ps_lookahead_workspace_bytes(int32_t n_inst, int32_t map_len);
+size_t ps_lookahead_workspace_bytes(int64_t n_rec, int32_t n_inst, int32_t map_len);
 int ps_lookahead_update(const int32_t* instance_id, const int32_t* start_iter,
                         const int32_t* prompt_tokens, const int32_t* i_begin, const int32_t* i_end,
                         const int32_t* sign, int64_t n_rec, int32_t n_inst, int32_t map_len,

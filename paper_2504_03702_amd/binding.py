@@ -70,7 +70,7 @@ def load_library() -> ctypes.CDLL:
     lib.ps_anticipate_static.restype = ctypes.c_int
     lib.ps_anticipate_static.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp]
     lib.ps_lookahead_workspace_bytes.restype = sz
-    lib.ps_lookahead_workspace_bytes.argtypes = [i32, i32]
+    lib.ps_lookahead_workspace_bytes.argtypes = [i64, i32, i32]
     lib.ps_lookahead_update.restype = ctypes.c_int
     lib.ps_lookahead_update.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp, vp]
     lib.ps_scaler_scan.restype = ctypes.c_int
@@ -226,8 +226,8 @@ def ps_anticipate_static(pred_tokens: torch.Tensor, instance_id: torch.Tensor, a
         "ps_anticipate_static")
 
 
-def ps_lookahead_workspace_bytes(n_inst: int, map_len: int) -> int:
-    return int(load_library().ps_lookahead_workspace_bytes(n_inst, map_len))
+def ps_lookahead_workspace_bytes(n_rec: int, n_inst: int, map_len: int) -> int:
+    return int(load_library().ps_lookahead_workspace_bytes(n_rec, n_inst, map_len))
 
 
 def ps_lookahead_update(instance_id: torch.Tensor, start_iter: torch.Tensor, prompt_tokens: torch.Tensor,

@@ -20,6 +20,16 @@
 // record applies its updates; one workgroup per instance scans its row, accumulates into the
 // caller's map and, if asked, writes the fraction of the instance's token capacity.  Integer
 // arithmetic throughout: the result is exact and independent of record order.
+//
+// Long record lists over maps whose rows fit a compute unit's LDS take another route, without global
+// atomics: the records are first binned by instance.  A workgroup of the binning kernel takes a chunk of
+// 8192 records, turns each into one 8-byte entry (first slot, slot after the last, offset, sign; tokens
+// beyond the map are summed per instance in LDS and added to overflow[] at the end), ranks the chunk's
+// entries per instance with an LDS counter each, and writes them to its own region of the workspace
+// grouped by instance, with the region's per-instance boundaries in a table.  Then one workgroup per
+// instance walks the table, applies its entries to an LDS row (offset differences in 64 bits, slope
+// differences in 32: nothing can overflow) and scans the row into the caller's map itself.  Every record
+// is read once (24 bytes), written once as an entry and read once more (8 bytes each).
 #include "device_util.h"
 #include "internal.h"
 
@@ -111,11 +121,216 @@ __global__ __launch_bounds__(256) void lookahead_scan_kernel(const long long* __
     }
 }
 
+
+// ---- binned route -----------------------------------------------------------------------------------
+const int kBinThreads = 1024;
+const int kBinPerThread = 8;
+const int kBinChunk = kBinThreads * kBinPerThread;       // records per binning workgroup
+const int kBinMaxInst = 4096;                            // instance counters of a chunk live in LDS
+const int kRowLdsBytes = 150 * 1024;                     // LDS a map row may take (12 bytes per slot)
+const int64_t kBinMinRecords = 65536;                    // shorter lists do not pay for the extra pass
+const int64_t kBinPart = (int64_t)1 << 26;               // records per part (bounds the workspace)
+
+// entry: bits 0..16 first slot (map_len: none), 17..33 slot after the last (map_len: none),
+//        34..52 offset + 2^18, bit 53 set for sign -1
+__device__ __forceinline__ unsigned long long pack_entry(unsigned lo, unsigned hi, int offset, int sg) {
+    return (unsigned long long)lo | ((unsigned long long)hi << 17) | ((unsigned long long)(unsigned)(offset + (1 << 18)) << 34) |
+           ((unsigned long long)(sg < 0 ? 1u : 0u) << 53);
+}
+
+__global__ __launch_bounds__(kBinThreads) void lookahead_bin_kernel(
+    const int32_t* __restrict__ instance_id, const int32_t* __restrict__ start_iter,
+    const int32_t* __restrict__ prompt_tokens, const int32_t* __restrict__ i_begin,
+    const int32_t* __restrict__ i_end, const int32_t* __restrict__ sign, int64_t n, int64_t first_index, int n_inst,
+    int map_len, unsigned long long* __restrict__ entries, int32_t* __restrict__ table, int64_t* __restrict__ overflow,
+    ps_status* st) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    long long* s_ovf = (long long*)lds_raw;                               // [n_inst] tokens beyond the map
+    int* s_cnt = (int*)(s_ovf + n_inst);                                  // [n_inst] entries per instance, then their starts
+    int* s_scan = s_cnt + n_inst;                                         // [kBinThreads]
+    const int tid = threadIdx.x;
+    const int64_t chunk = blockIdx.x, base = chunk * kBinChunk;
+    for (int i = tid; i < n_inst; i += kBinThreads) { s_ovf[i] = 0; s_cnt[i] = 0; }
+    __syncthreads();
+    unsigned long long ent[kBinPerThread];
+    int inst[kBinPerThread], rank[kBinPerThread];
+#pragma unroll
+    for (int u = 0; u < kBinPerThread; ++u) {
+        // consecutive threads take consecutive records (coalesced 4-byte loads, kBinPerThread rounds)
+        const int64_t r = base + (int64_t)u * kBinThreads + tid;
+        inst[u] = -1;
+        if (r >= n) continue;
+        const int k = instance_id[r], s = start_iter[r], P = prompt_tokens[r];
+        const int b = i_begin[r], e = i_end[r], sg = sign[r];
+        if ((unsigned)k >= (unsigned)n_inst || (unsigned)s >= (unsigned)map_len || (unsigned)P >= (unsigned)PS_MAX_PROMPT || b < 0 ||
+            e < b || e > PS_MAX_ITER || (sg != 1 && sg != -1)) {
+            report_fault(st, PS_ST_BAD_RECORD, first_index + r);
+            continue;
+        }
+        if (b == e) continue;
+        const int64_t lo = (int64_t)s + b, hi = (int64_t)s + e;
+        if (hi > map_len && overflow) {
+            // iterations io .. e - 1 fall beyond the map: c of them, sum of (P + i) in closed form
+            const long long io = max((long long)b, (long long)map_len - s), c = e - io;
+            const long long sum = c * P + (io + e - 1) * c / 2;
+            atomicAdd((unsigned long long*)&s_ovf[k], (unsigned long long)((long long)sg * sum));
+        }
+        if (lo >= map_len) continue;                                      // nothing of it inside the map
+        ent[u] = pack_entry((unsigned)lo, (unsigned)min(hi, (int64_t)map_len), P - s, sg);
+        inst[u] = k;
+        rank[u] = atomicAdd(&s_cnt[k], 1);
+    }
+    __syncthreads();
+    // exclusive scan of the per-instance counts: each thread a run of instances, then the threads' totals
+    const int per = (n_inst + kBinThreads - 1) / kBinThreads;
+    const int k0 = min(tid * per, n_inst), k1 = min(k0 + per, n_inst);
+    int run = 0;
+    for (int k = k0; k < k1; ++k) run += s_cnt[k];
+    s_scan[tid] = run;
+    __syncthreads();
+    for (int d = 1; d < kBinThreads; d <<= 1) {
+        const int a = tid >= d ? s_scan[tid - d] : 0;
+        __syncthreads();
+        s_scan[tid] += a;
+        __syncthreads();
+    }
+    int at = s_scan[tid] - run;
+    int32_t* trow = table + chunk * (int64_t)(n_inst + 1);
+    for (int k = k0; k < k1; ++k) {
+        const int c = s_cnt[k];
+        s_cnt[k] = at;
+        trow[k] = at;
+        at += c;
+    }
+    if (tid == kBinThreads - 1) trow[n_inst] = s_scan[kBinThreads - 1];
+    __syncthreads();
+    unsigned long long* out = entries + base;
+#pragma unroll
+    for (int u = 0; u < kBinPerThread; ++u)
+        if (inst[u] >= 0) out[s_cnt[inst[u]] + rank[u]] = ent[u];
+    if (overflow)
+        for (int i = tid; i < n_inst; i += kBinThreads)
+            if (s_ovf[i] != 0) atomicAdd((unsigned long long*)(overflow + i), (unsigned long long)s_ovf[i]);
+}
+
+// One workgroup per instance: its entries from every chunk into an LDS row, then the scan of that row
+// into the caller's map (same arithmetic as lookahead_scan_kernel).
+__global__ __launch_bounds__(1024) void lookahead_consume_kernel(
+    const unsigned long long* __restrict__ entries, const int32_t* __restrict__ table, int64_t n_chunks, int n_inst,
+    int map_len, int32_t* __restrict__ kv_tokens, const int32_t* __restrict__ capacity, float* __restrict__ fraction,
+    ps_status* st) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    long long* s_off = (long long*)lds_raw;                               // [map_len] offset differences
+    int* s_slp = (int*)(s_off + map_len);                                 // [map_len] slope differences
+    __shared__ long long s_w0[16], s_w1[16];
+    const int k = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < map_len; i += 1024) { s_off[i] = 0; s_slp[i] = 0; }
+    __syncthreads();
+    // wavefront w takes chunks w, w + 16, ...; the bounds of 64 of its chunks are fetched together (one per lane)
+    for (int64_t c0 = wave; c0 < n_chunks; c0 += 16 * 64) {
+        const int64_t mine = c0 + 16 * (int64_t)lane;
+        int seg_b = 0, seg_e = 0;
+        if (mine < n_chunks) {
+            const int32_t* trow = table + mine * (int64_t)(n_inst + 1);
+            seg_b = trow[k];
+            seg_e = trow[k + 1];
+        }
+        for (int j = 0; j < 64; ++j) {
+            const int64_t c = c0 + 16 * (int64_t)j;
+            if (c >= n_chunks) break;                                     // uniform
+            const int b = __shfl(seg_b, j, 64), e = __shfl(seg_e, j, 64);
+            const unsigned long long* src = entries + c * kBinChunk;
+            for (int i = b + lane; i < e; i += 64) {
+                const unsigned long long v = src[i];
+                const unsigned lo = (unsigned)(v & 0x1ffffu), hi = (unsigned)((v >> 17) & 0x1ffffu);
+                const long long off = (long long)((v >> 34) & 0x7ffffu) - (1 << 18);
+                const bool neg = (v >> 53) & 1u;
+                const long long a = neg ? -off : off;                     // sign * (P - s)
+                const int sl = neg ? -1 : 1;
+                atomicAdd((unsigned long long*)&s_off[lo], (unsigned long long)a);
+                atomicAdd(&s_slp[lo], sl);
+                if (hi < (unsigned)map_len) {
+                    atomicAdd((unsigned long long*)&s_off[hi], (unsigned long long)(-a));
+                    atomicAdd(&s_slp[hi], -sl);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    int32_t* out = kv_tokens + (int64_t)k * map_len;
+    float* frow = fraction ? fraction + (int64_t)k * map_len : nullptr;
+    const int cap = fraction ? capacity[k] : 1;
+    const float cap_f = cap >= 1 ? (float)cap : __builtin_nanf("");      // no capacity: fractions are NaN
+    long long carry0 = 0, carry1 = 0;
+    for (int t0 = 0; t0 < map_len; t0 += 4096) {
+        const int t = t0 + 4 * tid;
+        long long a0[4], a1[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            a0[c] = t + c < map_len ? s_off[t + c] : 0;
+            a1[c] = t + c < map_len ? (long long)s_slp[t + c] : 0;
+        }
+#pragma unroll
+        for (int c = 1; c < 4; ++c) { a0[c] += a0[c - 1]; a1[c] += a1[c - 1]; }
+        long long i0 = a0[3], i1 = a1[3];
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const long long u0 = __shfl_up(i0, o, 64), u1 = __shfl_up(i1, o, 64);
+            if (lane >= o) { i0 += u0; i1 += u1; }
+        }
+        if (lane == 63) { s_w0[wave] = i0; s_w1[wave] = i1; }
+        __syncthreads();
+        long long before0 = carry0 + i0 - a0[3], before1 = carry1 + i1 - a1[3];
+        long long tot0 = 0, tot1 = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < wave) { before0 += s_w0[w]; before1 += s_w1[w]; }
+            tot0 += s_w0[w];
+            tot1 += s_w1[w];
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (t + c < map_len) {
+                const long long nv = (long long)out[t + c] + (before0 + a0[c]) + (long long)(t + c) * (before1 + a1[c]);
+                if (nv > 2147483647ll || nv < -2147483648ll) report_fault(st, PS_ST_RANGE, -1);
+                out[t + c] = (int32_t)(uint32_t)(unsigned long long)nv;
+                if (frow) frow[t + c] = (float)nv / cap_f;
+            }
+        }
+        carry0 += tot0;
+        carry1 += tot1;
+        __syncthreads();
+    }
+}
+
+// Layout of the workspace: the difference array of the atomic route, then the binned route's entries and table.
+struct LookaheadPlan {
+    bool binned;                 // the call qualifies for the binned route
+    size_t diff_bytes, entries_at, entries_bytes, table_at, table_bytes, total_bytes;
+    int64_t part;                // records per part of the route taken
+};
+
+LookaheadPlan plan_lookahead(int64_t n_rec, int n_inst, int map_len) {
+    LookaheadPlan p;
+    p.diff_bytes = align_up((size_t)n_inst * (size_t)map_len * 8, 256);
+    p.binned = n_rec >= kBinMinRecords && n_inst <= kBinMaxInst && (int64_t)map_len * 12 <= kRowLdsBytes;
+    p.part = p.binned ? kBinPart : (int64_t)1 << 22;
+    p.entries_at = p.diff_bytes;
+    p.entries_bytes = p.table_bytes = 0;
+    if (p.binned) {
+        const int64_t most = n_rec < kBinPart ? n_rec : kBinPart;
+        const int64_t chunks = (most + kBinChunk - 1) / kBinChunk;
+        p.entries_bytes = align_up((size_t)chunks * kBinChunk * 8, 256);
+        p.table_bytes = align_up((size_t)chunks * (size_t)(n_inst + 1) * 4, 256);
+    }
+    p.table_at = p.entries_at + p.entries_bytes;
+    p.total_bytes = p.table_at + p.table_bytes;
+    return p;
+}
 }  // namespace
 
-extern "C" size_t ps_lookahead_workspace_bytes(int32_t n_inst, int32_t map_len) {
-    if (n_inst < 1 || map_len < 1 || map_len > PS_MAX_ITER + 1) return 0;
-    return align_up((size_t)n_inst * (size_t)map_len * 8, 256);
+extern "C" size_t ps_lookahead_workspace_bytes(int64_t n_rec, int32_t n_inst, int32_t map_len) {
+    if (n_rec < 0 || n_inst < 1 || map_len < 1 || map_len > PS_MAX_ITER + 1) return 0;
+    return plan_lookahead(n_rec, n_inst, map_len).total_bytes;
 }
 
 extern "C" int ps_lookahead_update(const int32_t* instance_id, const int32_t* start_iter,
@@ -128,15 +343,40 @@ extern "C" int ps_lookahead_update(const int32_t* instance_id, const int32_t* st
     if (map_len > PS_MAX_ITER + 1) return PS_EUNSUPPORTED;
     if (n_rec > 0 && (!instance_id || !start_iter || !prompt_tokens || !i_begin || !i_end || !sign)) return PS_EINVAL;
     if (n_rec == 0 && !fraction) return PS_OK;
-    const size_t need = ps_lookahead_workspace_bytes(n_inst, map_len);
+    const LookaheadPlan plan = plan_lookahead(n_rec, n_inst, map_len);
+    const size_t need = plan.total_bytes;
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need) return PS_EWORKSPACE;
     hipStream_t s = (hipStream_t)hip_stream;
     (void)hipGetLastError();
-    const int64_t n16 = (int64_t)(need / 16);
+    const int64_t n16 = (int64_t)(plan.diff_bytes / 16);
     const unsigned clear_blocks = (unsigned)((n16 + 255) / 256 < 2048 ? (n16 + 255) / 256 : 2048);
-    // parts of at most kPart records: the packed differences of one slot cannot overflow their fields within a
-    // part (see the top of this file); the map accumulates, so the parts add up to the whole
-    const int64_t kPart = (int64_t)1 << 22;
+    if (plan.binned) {
+        static bool lds_attr_set = false;     // raising the limit twice is harmless, so no lock
+        if (!lds_attr_set) {
+            if (hipFuncSetAttribute((const void*)lookahead_consume_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kRowLdsBytes) != hipSuccess ||
+                hipFuncSetAttribute((const void*)lookahead_bin_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kBinMaxInst * 12 + kBinThreads * 4) != hipSuccess)
+                return PS_EHIP;
+            lds_attr_set = true;
+        }
+        unsigned long long* entries = (unsigned long long*)((uint8_t*)workspace + plan.entries_at);
+        int32_t* table = (int32_t*)((uint8_t*)workspace + plan.table_at);
+        for (int64_t at = 0; at < n_rec; at += plan.part) {
+            const int64_t n_part = n_rec - at < plan.part ? n_rec - at : plan.part;
+            const bool last = at + plan.part >= n_rec;
+            const int64_t chunks = (n_part + kBinChunk - 1) / kBinChunk;
+            hipLaunchKernelGGL(lookahead_bin_kernel, dim3((unsigned)chunks), dim3(kBinThreads),
+                               (size_t)n_inst * 12 + kBinThreads * 4, s, instance_id + at, start_iter + at, prompt_tokens + at,
+                               i_begin + at, i_end + at, sign + at, n_part, at, n_inst, map_len, entries, table, overflow, status);
+            hipLaunchKernelGGL(lookahead_consume_kernel, dim3((unsigned)n_inst), dim3(1024), (size_t)map_len * 12, s, entries,
+                               table, chunks, n_inst, map_len, kv_tokens, capacity, last ? fraction : nullptr, status);
+        }
+        return hipGetLastError() == hipSuccess ? PS_OK : PS_EHIP;
+    }
+    // parts of at most plan.part records: the packed differences of one slot cannot overflow their fields within
+    // a part (see the top of this file); the map accumulates, so the parts add up to the whole
+    const int64_t kPart = plan.part;
     for (int64_t at = 0; at < n_rec || at == 0; at += kPart) {
         const int64_t n_part = n_rec - at < kPart ? n_rec - at : kPart;
         const bool last = at + kPart >= n_rec;

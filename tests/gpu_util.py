@@ -60,7 +60,7 @@ def run_lookahead(cols, n_inst, map_len, kv=None, overflow=None, capacity=None, 
             else torch.from_numpy(np.ascontiguousarray(overflow, np.int64)).to(dev)
     cap_t = None if capacity is None else t(capacity)
     frac_t = torch.full((n_inst * map_len,), -1.0, dtype=torch.float32, device=dev) if want_fraction else None
-    ws = ps.alloc_workspace(ps.ps_lookahead_workspace_bytes(n_inst, map_len), dev)
+    ws = ps.alloc_workspace(ps.ps_lookahead_workspace_bytes(len(cols[0]), n_inst, map_len), dev)
     ws.fill_(0xA5)                               # the library must not rely on a clean workspace
     st = ps.new_status(dev)
     ps.ps_lookahead_update(*[t(c) for c in cols], n_inst, map_len, kv_t, ovf_t, ws, cap_t, frac_t, st)

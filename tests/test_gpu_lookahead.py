@@ -107,7 +107,7 @@ def test_no_records_no_overflow_array_and_fraction_only():
     np.testing.assert_allclose(frac[[0, 2]], ol.fraction(kv[[0, 2]], cap[[0, 2]]), rtol=2.0 ** -23)
     # argument checks
     z = torch.zeros(4, dtype=torch.int32, device=dev)
-    ws = ps.alloc_workspace(ps.ps_lookahead_workspace_bytes(1, 4), dev)
+    ws = ps.alloc_workspace(ps.ps_lookahead_workspace_bytes(4, 1, 4), dev)
     with pytest.raises(ps.PsError) as e:
         ps.ps_lookahead_update(z[:1], z[:1], z[:1], z[:1], z[:1], z[:1], 1, 4, z, None, ws[:16])
     assert e.value.code == -5            # PS_EWORKSPACE
@@ -115,7 +115,7 @@ def test_no_records_no_overflow_array_and_fraction_only():
         ps.ps_lookahead_update(z[:1], z[:1], z[:1], z[:1], z[:1], z[:1], 1, 4, z, None, ws,
                                fraction=torch.zeros(4, device=dev))
     assert e.value.code == -1            # PS_EINVAL
-    assert ps.ps_lookahead_workspace_bytes(1, 65537) == 0 and ps.ps_lookahead_workspace_bytes(0, 8) == 0
+    assert ps.ps_lookahead_workspace_bytes(4, 1, 65537) == 0 and ps.ps_lookahead_workspace_bytes(4, 0, 8) == 0
 
 
 def run_scaler(kv, cap, window, dev="cuda:0", **pct):
@@ -163,12 +163,14 @@ def test_scaler_boundaries_and_scale_down():
     assert abs(got[5] - (4 - (0.299 + 0.05 + 0.298 + 0.025) / 0.3)) < 1e-12
 
 
-def test_all_requests_admitted_at_the_maps_origin():
+@pytest.mark.parametrize("map_len", [8, 16384])
+def test_all_requests_admitted_at_the_maps_origin(map_len):
     """The paper's own use: every request enters its instance's map at the origin once its prefill is done, so
     all records of a rebuild start in slot 0.  Nine million of them on one instance (more than one packed
     difference word could count at once: the call is folded in parts), with cancelling removals mixed in;
-    a second, small instance beside it.  Bit-exact against the oracle."""
-    print("lookahead 9 M records at slot 0", flush=True)
+    a second, small instance beside it.  Bit-exact against the oracle.  The short map takes the binned route
+    (wide counters in LDS), the long one the packed global counters, folded in parts."""
+    print(f"lookahead 9 M records at slot 0, map_len {map_len}", flush=True)
     n = 9_000_000
     rng = np.random.default_rng(21)
     inst = np.zeros(n, np.int32)
@@ -180,7 +182,30 @@ def test_all_requests_admitted_at_the_maps_origin():
     i_end = rng.integers(1, 5, n).astype(np.int32)
     sign = np.where(rng.random(n) < 0.45, -1, 1).astype(np.int32)
     cols = [inst, start, prompt, i_begin, i_end, sign]
-    (kv, ovf, _, flags, _), (rkv, rovf, rst, _) = both(cols, 2, 8)
+    (kv, ovf, _, flags, _), (rkv, rovf, rst, _) = both(cols, 2, map_len)
     assert rst == 0
     assert (flags & ~ps.PS_ST_RANGE) == 0                   # (an intermediate part may leave the int32 range and return)
     assert np.array_equal(kv, rkv) and np.array_equal(ovf, rovf)
+
+
+@pytest.mark.parametrize("n,K,map_len", [(100_003, 37, 1000), (65_536, 1, 12_800), (70_001, 4096, 5), (200_000, 300, 4097)])
+def test_binned_route_odd_shapes_faults_and_accumulation(n, K, map_len):
+    """Long record lists (binned by instance, folded in LDS): ragged last chunk, instance counts and map lengths
+    that divide nothing, ramps crossing the end of the map, faulty records in the middle, accumulation into a map
+    that already holds values, with and without an overflow array."""
+    print(f"lookahead binned n={n} K={K} map_len={map_len}", flush=True)
+    rng = np.random.default_rng(n + K)
+    cols = [rng.integers(0, K, n), rng.integers(0, map_len, n), rng.integers(0, 3000, n),
+            rng.integers(0, 30, n), None, rng.choice([-1, 1], n)]
+    cols[4] = cols[3] + rng.integers(0, min(2 * map_len, 65535 - 30) + 1, n)
+    cols = [np.asarray(c, np.int32) for c in cols]
+    cols[0][[17, n - 1]] = [K, -1]
+    cols[2][n // 2] = 1 << 20
+    cols[5][n // 3] = 2
+    kv0 = rng.integers(-1000, 1000, (K, map_len)).astype(np.int32)
+    ovf0 = rng.integers(-10**9, 10**9, K).astype(np.int64)
+    (kv, ovf, _, flags, first), (rkv, rovf, rst, rfirst) = both(cols, K, map_len, kv=kv0, overflow=ovf0)
+    assert rst == 1 and flags == ps.PS_ST_BAD_RECORD and first == rfirst == 17
+    assert np.array_equal(kv, rkv) and np.array_equal(ovf, rovf)
+    kv2, none, _, _, _ = run_lookahead(cols, K, map_len, kv=kv0, with_overflow=False)
+    assert none is None and np.array_equal(kv2, rkv)
