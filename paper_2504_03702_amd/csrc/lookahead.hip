@@ -123,8 +123,8 @@ __global__ __launch_bounds__(256) void lookahead_scan_kernel(const long long* __
 
 
 // ---- binned route -----------------------------------------------------------------------------------
-const int kBinThreads = 1024;
-const int kBinPerThread = 8;
+const int kBinThreads = 512;
+const int kBinPerThread = 16;
 const int kBinChunk = kBinThreads * kBinPerThread;       // records per binning workgroup
 const int kBinMaxInst = 4096;                            // instance counters of a chunk live in LDS
 const int kRowLdsBytes = 150 * 1024;                     // LDS a map row may take (12 bytes per slot)
@@ -138,6 +138,8 @@ __device__ __forceinline__ unsigned long long pack_entry(unsigned lo, unsigned h
            ((unsigned long long)(sg < 0 ? 1u : 0u) << 53);
 }
 
+// VEC: the six arrays are 16-byte aligned, a thread takes four consecutive records per load.
+template <bool VEC>
 __global__ __launch_bounds__(kBinThreads) void lookahead_bin_kernel(
     const int32_t* __restrict__ instance_id, const int32_t* __restrict__ start_iter,
     const int32_t* __restrict__ prompt_tokens, const int32_t* __restrict__ i_begin,
@@ -145,56 +147,84 @@ __global__ __launch_bounds__(kBinThreads) void lookahead_bin_kernel(
     int map_len, unsigned long long* __restrict__ entries, int32_t* __restrict__ table, int64_t* __restrict__ overflow,
     ps_status* st) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    long long* s_ovf = (long long*)lds_raw;                               // [n_inst] tokens beyond the map
+    unsigned long long* s_ent = (unsigned long long*)lds_raw;             // [kBinChunk] the chunk's entries, grouped by instance
+    long long* s_ovf = (long long*)(s_ent + kBinChunk);                   // [n_inst] tokens beyond the map
     int* s_cnt = (int*)(s_ovf + n_inst);                                  // [n_inst] entries per instance, then their starts
-    int* s_scan = s_cnt + n_inst;                                         // [kBinThreads]
-    const int tid = threadIdx.x;
+    __shared__ int s_wave[kBinThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t chunk = blockIdx.x, base = chunk * kBinChunk;
     for (int i = tid; i < n_inst; i += kBinThreads) { s_ovf[i] = 0; s_cnt[i] = 0; }
     __syncthreads();
     unsigned long long ent[kBinPerThread];
     int inst[kBinPerThread], rank[kBinPerThread];
-#pragma unroll
-    for (int u = 0; u < kBinPerThread; ++u) {
-        // consecutive threads take consecutive records (coalesced 4-byte loads, kBinPerThread rounds)
-        const int64_t r = base + (int64_t)u * kBinThreads + tid;
+    // One record: checks, its tokens beyond the map, its entry and the entry's rank among its instance's
+    auto take = [&](int u, int64_t r, int k, int s, int P, int b, int e, int sg) {
         inst[u] = -1;
-        if (r >= n) continue;
-        const int k = instance_id[r], s = start_iter[r], P = prompt_tokens[r];
-        const int b = i_begin[r], e = i_end[r], sg = sign[r];
         if ((unsigned)k >= (unsigned)n_inst || (unsigned)s >= (unsigned)map_len || (unsigned)P >= (unsigned)PS_MAX_PROMPT || b < 0 ||
             e < b || e > PS_MAX_ITER || (sg != 1 && sg != -1)) {
             report_fault(st, PS_ST_BAD_RECORD, first_index + r);
-            continue;
+            return;
         }
-        if (b == e) continue;
-        const int64_t lo = (int64_t)s + b, hi = (int64_t)s + e;
+        if (b == e) return;
+        const int lo = s + b, hi = s + e;                                 // both below 2^17
         if (hi > map_len && overflow) {
             // iterations io .. e - 1 fall beyond the map: c of them, sum of (P + i) in closed form
-            const long long io = max((long long)b, (long long)map_len - s), c = e - io;
+            const long long io = max(b, map_len - s), c = e - io;
             const long long sum = c * P + (io + e - 1) * c / 2;
             atomicAdd((unsigned long long*)&s_ovf[k], (unsigned long long)((long long)sg * sum));
         }
-        if (lo >= map_len) continue;                                      // nothing of it inside the map
-        ent[u] = pack_entry((unsigned)lo, (unsigned)min(hi, (int64_t)map_len), P - s, sg);
+        if (lo >= map_len) return;                                        // nothing of it inside the map
+        ent[u] = pack_entry((unsigned)lo, (unsigned)min(hi, map_len), P - s, sg);
         inst[u] = k;
         rank[u] = atomicAdd(&s_cnt[k], 1);
+    };
+    if (VEC && base + kBinChunk <= n) {
+        // whole chunk: a thread's u-th load covers records base + (u * kBinThreads + tid) * 4 .. + 3
+        constexpr int NV = kBinPerThread / 4;
+        int4 vk[NV], vs[NV], vp[NV], vb[NV], ve[NV], vg[NV];
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int64_t r = base + ((int64_t)u * kBinThreads + tid) * 4;
+            vk[u] = *(const int4*)(instance_id + r); vs[u] = *(const int4*)(start_iter + r);
+            vp[u] = *(const int4*)(prompt_tokens + r); vb[u] = *(const int4*)(i_begin + r);
+            ve[u] = *(const int4*)(i_end + r); vg[u] = *(const int4*)(sign + r);
+        }
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int64_t r = base + ((int64_t)u * kBinThreads + tid) * 4;
+            take(4 * u, r, vk[u].x, vs[u].x, vp[u].x, vb[u].x, ve[u].x, vg[u].x);
+            take(4 * u + 1, r + 1, vk[u].y, vs[u].y, vp[u].y, vb[u].y, ve[u].y, vg[u].y);
+            take(4 * u + 2, r + 2, vk[u].z, vs[u].z, vp[u].z, vb[u].z, ve[u].z, vg[u].z);
+            take(4 * u + 3, r + 3, vk[u].w, vs[u].w, vp[u].w, vb[u].w, ve[u].w, vg[u].w);
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < kBinPerThread; ++u) {
+            const int64_t r = base + (int64_t)u * kBinThreads + tid;
+            inst[u] = -1;
+            if (r < n) take(u, r, instance_id[r], start_iter[r], prompt_tokens[r], i_begin[r], i_end[r], sign[r]);
+        }
     }
     __syncthreads();
-    // exclusive scan of the per-instance counts: each thread a run of instances, then the threads' totals
+    // exclusive scan of the per-instance counts: each thread a run of instances, the threads' totals by
+    // wavefront shuffles, the wavefronts' totals through LDS
     const int per = (n_inst + kBinThreads - 1) / kBinThreads;
     const int k0 = min(tid * per, n_inst), k1 = min(k0 + per, n_inst);
     int run = 0;
     for (int k = k0; k < k1; ++k) run += s_cnt[k];
-    s_scan[tid] = run;
-    __syncthreads();
-    for (int d = 1; d < kBinThreads; d <<= 1) {
-        const int a = tid >= d ? s_scan[tid - d] : 0;
-        __syncthreads();
-        s_scan[tid] += a;
-        __syncthreads();
+    int incl = run;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += t;
     }
-    int at = s_scan[tid] - run;
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    int at = incl - run, total = 0;
+    for (int w = 0; w < kBinThreads / 64; ++w) {
+        if (w < wave) at += s_wave[w];
+        total += s_wave[w];
+    }
     int32_t* trow = table + chunk * (int64_t)(n_inst + 1);
     for (int k = k0; k < k1; ++k) {
         const int c = s_cnt[k];
@@ -202,12 +232,16 @@ __global__ __launch_bounds__(kBinThreads) void lookahead_bin_kernel(
         trow[k] = at;
         at += c;
     }
-    if (tid == kBinThreads - 1) trow[n_inst] = s_scan[kBinThreads - 1];
+    if (tid == 0) trow[n_inst] = total;
     __syncthreads();
-    unsigned long long* out = entries + base;
+    // grouped in LDS first, so that the chunk's region is written with whole 16-byte pieces per lane
 #pragma unroll
     for (int u = 0; u < kBinPerThread; ++u)
-        if (inst[u] >= 0) out[s_cnt[inst[u]] + rank[u]] = ent[u];
+        if (inst[u] >= 0) s_ent[s_cnt[inst[u]] + rank[u]] = ent[u];
+    __syncthreads();
+    ulonglong2* out = (ulonglong2*)(entries + base);
+    const ulonglong2* src = (const ulonglong2*)s_ent;
+    for (int i = tid; i < (total + 1) / 2; i += kBinThreads) out[i] = src[i];
     if (overflow)
         for (int i = tid; i < n_inst; i += kBinThreads)
             if (s_ovf[i] != 0) atomicAdd((unsigned long long*)(overflow + i), (unsigned long long)s_ovf[i]);
@@ -226,7 +260,21 @@ __global__ __launch_bounds__(1024) void lookahead_consume_kernel(
     const int k = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int i = tid; i < map_len; i += 1024) { s_off[i] = 0; s_slp[i] = 0; }
     __syncthreads();
-    // wavefront w takes chunks w, w + 16, ...; the bounds of 64 of its chunks are fetched together (one per lane)
+    auto apply = [&](unsigned long long v) {
+        const unsigned lo = (unsigned)(v & 0x1ffffu), hi = (unsigned)((v >> 17) & 0x1ffffu);
+        const long long off = (long long)((v >> 34) & 0x7ffffu) - (1 << 18);
+        const bool neg = (v >> 53) & 1u;
+        const long long a = neg ? -off : off;                             // sign * (P - s)
+        const int sl = neg ? -1 : 1;
+        atomicAdd((unsigned long long*)&s_off[lo], (unsigned long long)a);
+        atomicAdd(&s_slp[lo], sl);
+        if (hi < (unsigned)map_len) {
+            atomicAdd((unsigned long long*)&s_off[hi], (unsigned long long)(-a));
+            atomicAdd(&s_slp[hi], -sl);
+        }
+    };
+    // wavefront w takes chunks w, w + 16, ...; the bounds of 64 of its chunks are fetched together (one per
+    // lane), and the first 64 entries of eight chunks are requested before any is applied
     for (int64_t c0 = wave; c0 < n_chunks; c0 += 16 * 64) {
         const int64_t mine = c0 + 16 * (int64_t)lane;
         int seg_b = 0, seg_e = 0;
@@ -235,24 +283,23 @@ __global__ __launch_bounds__(1024) void lookahead_consume_kernel(
             seg_b = trow[k];
             seg_e = trow[k + 1];
         }
-        for (int j = 0; j < 64; ++j) {
-            const int64_t c = c0 + 16 * (int64_t)j;
-            if (c >= n_chunks) break;                                     // uniform
-            const int b = __shfl(seg_b, j, 64), e = __shfl(seg_e, j, 64);
-            const unsigned long long* src = entries + c * kBinChunk;
-            for (int i = b + lane; i < e; i += 64) {
-                const unsigned long long v = src[i];
-                const unsigned lo = (unsigned)(v & 0x1ffffu), hi = (unsigned)((v >> 17) & 0x1ffffu);
-                const long long off = (long long)((v >> 34) & 0x7ffffu) - (1 << 18);
-                const bool neg = (v >> 53) & 1u;
-                const long long a = neg ? -off : off;                     // sign * (P - s)
-                const int sl = neg ? -1 : 1;
-                atomicAdd((unsigned long long*)&s_off[lo], (unsigned long long)a);
-                atomicAdd(&s_slp[lo], sl);
-                if (hi < (unsigned)map_len) {
-                    atomicAdd((unsigned long long*)&s_off[hi], (unsigned long long)(-a));
-                    atomicAdd(&s_slp[hi], -sl);
-                }
+        constexpr int UC = 8;
+        for (int j0 = 0; j0 < 64; j0 += UC) {
+            if (c0 + 16 * (int64_t)j0 >= n_chunks) break;                 // uniform
+            int b[UC], e[UC];
+            unsigned long long first[UC];
+#pragma unroll
+            for (int u = 0; u < UC; ++u) {
+                b[u] = __shfl(seg_b, j0 + u, 64);                          // (chunks past the end: empty segments)
+                e[u] = __shfl(seg_e, j0 + u, 64);
+                const unsigned long long* src = entries + (c0 + 16 * (int64_t)(j0 + u)) * kBinChunk;
+                first[u] = b[u] + lane < e[u] ? src[b[u] + lane] : 0ull;
+            }
+#pragma unroll
+            for (int u = 0; u < UC; ++u) {
+                if (b[u] + lane < e[u]) apply(first[u]);
+                const unsigned long long* src = entries + (c0 + 16 * (int64_t)(j0 + u)) * kBinChunk;
+                for (int i = b[u] + 64 + lane; i < e[u]; i += 64) apply(src[i]);
             }
         }
     }
@@ -355,20 +402,29 @@ extern "C" int ps_lookahead_update(const int32_t* instance_id, const int32_t* st
         if (!lds_attr_set) {
             if (hipFuncSetAttribute((const void*)lookahead_consume_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     kRowLdsBytes) != hipSuccess ||
-                hipFuncSetAttribute((const void*)lookahead_bin_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kBinMaxInst * 12 + kBinThreads * 4) != hipSuccess)
+                hipFuncSetAttribute((const void*)lookahead_bin_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kBinChunk * 8 + kBinMaxInst * 12) != hipSuccess ||
+                hipFuncSetAttribute((const void*)lookahead_bin_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kBinChunk * 8 + kBinMaxInst * 12) != hipSuccess)
                 return PS_EHIP;
             lds_attr_set = true;
         }
         unsigned long long* entries = (unsigned long long*)((uint8_t*)workspace + plan.entries_at);
         int32_t* table = (int32_t*)((uint8_t*)workspace + plan.table_at);
+        const bool vec = (((uintptr_t)instance_id | (uintptr_t)start_iter | (uintptr_t)prompt_tokens | (uintptr_t)i_begin |
+                           (uintptr_t)i_end | (uintptr_t)sign) & 15) == 0;       // (parts start at multiples of 2^26 records)
         for (int64_t at = 0; at < n_rec; at += plan.part) {
             const int64_t n_part = n_rec - at < plan.part ? n_rec - at : plan.part;
             const bool last = at + plan.part >= n_rec;
             const int64_t chunks = (n_part + kBinChunk - 1) / kBinChunk;
-            hipLaunchKernelGGL(lookahead_bin_kernel, dim3((unsigned)chunks), dim3(kBinThreads),
-                               (size_t)n_inst * 12 + kBinThreads * 4, s, instance_id + at, start_iter + at, prompt_tokens + at,
-                               i_begin + at, i_end + at, sign + at, n_part, at, n_inst, map_len, entries, table, overflow, status);
+            if (vec)
+                hipLaunchKernelGGL(lookahead_bin_kernel<true>, dim3((unsigned)chunks), dim3(kBinThreads), (size_t)kBinChunk * 8 + (size_t)n_inst * 12, s,
+                                   instance_id + at, start_iter + at, prompt_tokens + at, i_begin + at, i_end + at, sign + at,
+                                   n_part, at, n_inst, map_len, entries, table, overflow, status);
+            else
+                hipLaunchKernelGGL(lookahead_bin_kernel<false>, dim3((unsigned)chunks), dim3(kBinThreads), (size_t)kBinChunk * 8 + (size_t)n_inst * 12, s,
+                                   instance_id + at, start_iter + at, prompt_tokens + at, i_begin + at, i_end + at, sign + at,
+                                   n_part, at, n_inst, map_len, entries, table, overflow, status);
             hipLaunchKernelGGL(lookahead_consume_kernel, dim3((unsigned)n_inst), dim3(1024), (size_t)map_len * 12, s, entries,
                                table, chunks, n_inst, map_len, kv_tokens, capacity, last ? fraction : nullptr, status);
         }

@@ -209,3 +209,28 @@ def test_binned_route_odd_shapes_faults_and_accumulation(n, K, map_len):
     assert np.array_equal(kv, rkv) and np.array_equal(ovf, rovf)
     kv2, none, _, _, _ = run_lookahead(cols, K, map_len, kv=kv0, with_overflow=False)
     assert none is None and np.array_equal(kv2, rkv)
+
+
+def test_binned_route_on_unaligned_arrays():
+    """Record arrays that start in the middle of a 16-byte group (views one element into a larger buffer)."""
+    n, K, map_len = 90_001, 20, 3000
+    rng = np.random.default_rng(5)
+    cols = [rng.integers(0, K, n), rng.integers(0, map_len, n), rng.integers(0, 3000, n),
+            rng.integers(0, 30, n), None, rng.choice([-1, 1], n)]
+    cols[4] = cols[3] + rng.integers(0, 2000, n)
+    cols = [np.asarray(c, np.int32) for c in cols]
+    dev = "cuda:0"
+    views = []
+    for c in cols:
+        buf = torch.zeros(n + 1, dtype=torch.int32, device=dev)
+        buf[1:] = torch.from_numpy(c).to(dev)
+        views.append(buf[1:])
+    assert views[0].data_ptr() % 16 == 4
+    kv = torch.zeros(K * map_len, dtype=torch.int32, device=dev)
+    ovf = torch.zeros(K, dtype=torch.int64, device=dev)
+    ws = ps.alloc_workspace(ps.ps_lookahead_workspace_bytes(n, K, map_len), dev)
+    st = ps.new_status(dev)
+    ps.ps_lookahead_update(*views, K, map_len, kv, ovf, ws, status=st)
+    assert ps.ps_status_read(st)[0] == 0
+    rkv, rovf, _, _ = ol.lookahead_update(*cols, K, map_len)
+    assert np.array_equal(kv.cpu().numpy().reshape(K, map_len), rkv) and np.array_equal(ovf.cpu().numpy(), rovf)
