@@ -72,12 +72,16 @@ __global__ __launch_bounds__(256) void forecast_kernel(const float* __restrict__
                 const float v = t < k ? hist[t] : y[kind][0];
                 const float x = (v - lo) / span;
                 float a = 0.f;
-                if (unit) for (int j = 0; j < H; ++j) a = fmaf(W_mh[j * H + lane], s_h[wave][j], a);
+                if (unit) {
+#pragma unroll 16
+                    for (int j = 0; j < H; ++j) a = fmaf(W_mh[j * H + lane], s_h[wave][j], a);
+                }
                 s_m[wave][lane] = unit ? (w_mx[lane] * x) * a : 0.f;
                 __syncthreads();
                 if (unit) {
                     float hh = fmaf(w_hx[lane], x, b_h[lane]), gi = fmaf(w_ix[lane], x, b_i[lane]);
                     float go = fmaf(w_ox[lane], x, b_o[lane]), gf = fmaf(w_fx[lane], x, b_f[lane]);
+#pragma unroll 8
                     for (int j = 0; j < H; ++j) {
                         const float mj = s_m[wave][j];
                         hh = fmaf(W_hm[j * H + lane], mj, hh);

@@ -144,8 +144,8 @@ __global__ __launch_bounds__(kBinThreads) void lookahead_bin_kernel(
     const int32_t* __restrict__ instance_id, const int32_t* __restrict__ start_iter,
     const int32_t* __restrict__ prompt_tokens, const int32_t* __restrict__ i_begin,
     const int32_t* __restrict__ i_end, const int32_t* __restrict__ sign, int64_t n, int64_t first_index, int n_inst,
-    int map_len, unsigned long long* __restrict__ entries, int32_t* __restrict__ table, int64_t* __restrict__ overflow,
-    ps_status* st) {
+    int map_len, unsigned long long* __restrict__ entries, int32_t* __restrict__ table, int64_t n_chunks,
+    int64_t* __restrict__ overflow, ps_status* st) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     unsigned long long* s_ent = (unsigned long long*)lds_raw;             // [kBinChunk] the chunk's entries, grouped by instance
     long long* s_ovf = (long long*)(s_ent + kBinChunk);                   // [n_inst] tokens beyond the map
@@ -225,14 +225,16 @@ __global__ __launch_bounds__(kBinThreads) void lookahead_bin_kernel(
         if (w < wave) at += s_wave[w];
         total += s_wave[w];
     }
-    int32_t* trow = table + chunk * (int64_t)(n_inst + 1);
+    // table[k][chunk] = where instance k's entries start in this chunk's region (row n_inst: where they all end);
+    // instance-major, so that the workgroup that folds instance k reads two contiguous rows
+    int32_t* tcol = table + chunk;
     for (int k = k0; k < k1; ++k) {
         const int c = s_cnt[k];
         s_cnt[k] = at;
-        trow[k] = at;
+        tcol[(int64_t)k * n_chunks] = at;
         at += c;
     }
-    if (tid == 0) trow[n_inst] = total;
+    if (tid == 0) tcol[(int64_t)n_inst * n_chunks] = total;
     __syncthreads();
     // grouped in LDS first, so that the chunk's region is written with whole 16-byte pieces per lane
 #pragma unroll
@@ -273,32 +275,31 @@ __global__ __launch_bounds__(1024) void lookahead_consume_kernel(
             atomicAdd(&s_slp[hi], -sl);
         }
     };
-    // wavefront w takes chunks w, w + 16, ...; the bounds of 64 of its chunks are fetched together (one per
-    // lane), and the first 64 entries of eight chunks are requested before any is applied
-    for (int64_t c0 = wave; c0 < n_chunks; c0 += 16 * 64) {
-        const int64_t mine = c0 + 16 * (int64_t)lane;
+    // wavefront w takes chunks 64 w .. 64 w + 63, then 1024 further on; their bounds are fetched together (one chunk
+    // per lane), and the first 64 entries of eight chunks are requested before any is applied
+    for (int64_t c0 = (int64_t)wave * 64; c0 < n_chunks; c0 += 16 * 64) {
+        const int64_t mine = c0 + lane;
         int seg_b = 0, seg_e = 0;
         if (mine < n_chunks) {
-            const int32_t* trow = table + mine * (int64_t)(n_inst + 1);
-            seg_b = trow[k];
-            seg_e = trow[k + 1];
+            seg_b = table[(int64_t)k * n_chunks + mine];
+            seg_e = table[(int64_t)(k + 1) * n_chunks + mine];
         }
         constexpr int UC = 8;
         for (int j0 = 0; j0 < 64; j0 += UC) {
-            if (c0 + 16 * (int64_t)j0 >= n_chunks) break;                 // uniform
+            if (c0 + j0 >= n_chunks) break;                               // uniform
             int b[UC], e[UC];
             unsigned long long first[UC];
 #pragma unroll
             for (int u = 0; u < UC; ++u) {
                 b[u] = __shfl(seg_b, j0 + u, 64);                          // (chunks past the end: empty segments)
                 e[u] = __shfl(seg_e, j0 + u, 64);
-                const unsigned long long* src = entries + (c0 + 16 * (int64_t)(j0 + u)) * kBinChunk;
+                const unsigned long long* src = entries + (c0 + j0 + u) * kBinChunk;
                 first[u] = b[u] + lane < e[u] ? src[b[u] + lane] : 0ull;
             }
 #pragma unroll
             for (int u = 0; u < UC; ++u) {
                 if (b[u] + lane < e[u]) apply(first[u]);
-                const unsigned long long* src = entries + (c0 + 16 * (int64_t)(j0 + u)) * kBinChunk;
+                const unsigned long long* src = entries + (c0 + j0 + u) * kBinChunk;
                 for (int i = b[u] + 64 + lane; i < e[u]; i += 64) apply(src[i]);
             }
         }
@@ -420,11 +421,11 @@ extern "C" int ps_lookahead_update(const int32_t* instance_id, const int32_t* st
             if (vec)
                 hipLaunchKernelGGL(lookahead_bin_kernel<true>, dim3((unsigned)chunks), dim3(kBinThreads), (size_t)kBinChunk * 8 + (size_t)n_inst * 12, s,
                                    instance_id + at, start_iter + at, prompt_tokens + at, i_begin + at, i_end + at, sign + at,
-                                   n_part, at, n_inst, map_len, entries, table, overflow, status);
+                                   n_part, at, n_inst, map_len, entries, table, chunks, overflow, status);
             else
                 hipLaunchKernelGGL(lookahead_bin_kernel<false>, dim3((unsigned)chunks), dim3(kBinThreads), (size_t)kBinChunk * 8 + (size_t)n_inst * 12, s,
                                    instance_id + at, start_iter + at, prompt_tokens + at, i_begin + at, i_end + at, sign + at,
-                                   n_part, at, n_inst, map_len, entries, table, overflow, status);
+                                   n_part, at, n_inst, map_len, entries, table, chunks, overflow, status);
             hipLaunchKernelGGL(lookahead_consume_kernel, dim3((unsigned)n_inst), dim3(1024), (size_t)map_len * 12, s, entries,
                                table, chunks, n_inst, map_len, kv_tokens, capacity, last ? fraction : nullptr, status);
         }
