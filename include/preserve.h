@@ -237,7 +237,9 @@ int ps_scaler_scan(const int32_t* kv_tokens, const int32_t* capacity, int32_t n_
  * All arrays are device pointers.  One workgroup walks the batch: n_inst <= 1024 and
  * n_inst * (20 + 4 * window) bytes plus 21 KB must fit in 160 KB of LDS (PS_EUNSUPPORTED otherwise).
  * The full-length maps are brought up to date by passing `assigned` as instance_id to
- * ps_lookahead_update().  Errors: PS_EINVAL, PS_EUNSUPPORTED, PS_EHIP. */
+ * ps_lookahead_update().  A window value that leaves the int32 range keeps its low 32 bits (PS_ST_RANGE);
+ * the flag is also raised, conservatively, once the largest window value so far plus a request's P + window
+ * reaches 2^31.  Errors: PS_EINVAL, PS_EUNSUPPORTED, PS_EHIP. */
 int ps_route(const int32_t* prompt_tokens, const int32_t* pred_tokens, int32_t n_req, int32_t n_inst,
              int32_t window, int32_t* window_tokens, const int32_t* capacity, int64_t* queued_p,
              int64_t* current_d, int32_t t_mem_pct, int32_t beta, int32_t* assigned, int64_t* score100,

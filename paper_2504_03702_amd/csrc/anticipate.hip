@@ -342,6 +342,26 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_window_kernel(
     const int a0 = max(arrival_bucket[begin], 0);
     if (tid < 2) s_flag[tid] = 0;
     __syncthreads();
+    {
+        // A look at the slice's first records before anything is set up: a stream in no particular order shows a
+        // valid arrival bucket outside the window at once, and the workgroup leaves without clearing its counters.
+        // (Invalid buckets are not counted: such records are skipped, not folded.)
+        const int64_t probe = begin + (int64_t)tid * 4;
+        bool far = false;
+        if (probe + 4 <= end) {
+            const int4 av = *(const int4*)(arrival_bucket + probe);
+            const int aa[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                far |= (unsigned)aa[c] < (unsigned)horizon && (unsigned)(aa[c] - a0) >= (unsigned)w_buckets;
+        }
+        if (__any(far) && lane == 0) s_flag[1] = 1;
+        __syncthreads();
+        if (s_flag[1]) {                                      // uniform
+            if (tid == 0) worigin[slice] = kGaveUp;
+            return;
+        }
+    }
     for (int i = tid; i < n_inst * w_buckets; i += kScatterThreads) s_diff[i] = 0;
     for (int i = tid; i < n_inst; i += kScatterThreads) {
         s_ovf[i] = 0;

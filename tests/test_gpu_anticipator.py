@@ -88,6 +88,41 @@ def test_arrival_order_with_exceptions():
         check(inp)
 
 
+def test_long_streams_in_any_order_with_exceptions():
+    """Long streams in no particular order: the windowed kernel sees at once that they are not in arrival order
+    and leaves them to the general kernel.  Plain, accumulated, without rates, with large quotients, with the
+    largest predictions, with faulty records and a row without a usable rate, and on other shapes."""
+    rng = np.random.default_rng(12)
+    base = wl.make_anticipator_inputs("stream", seed=6, n=500_000)
+    print("anticipator any order: plain", flush=True)
+    load, ovf, flags = check(base)
+    assert flags == 0
+    check(base, load.copy(), ovf + 3)                                  # accumulated a second time
+    print("anticipator any order: no rates (spread to the end of the horizon)", flush=True)
+    check(dataclasses.replace(base, rate=None))
+    print("anticipator any order: fast instances (large quotients)", flush=True)
+    check(dataclasses.replace(base, rate=np.full(base.n_inst, 5000, np.int32),
+                              pred_tokens=rng.integers(1, 4097, base.pred_tokens.size).astype(np.int32)))
+    print("anticipator any order: predictions above 32767", flush=True)
+    d = base.pred_tokens.copy()
+    d[[7, 250_000, 499_999]] = [40_000, 65_535, 32_768]
+    check(dataclasses.replace(base, pred_tokens=d))
+    print("anticipator any order: faulty records and a row without a rate", flush=True)
+    k = base.instance_id.copy(); d = base.pred_tokens.copy(); a = base.arrival_bucket.copy()
+    k[[3, 400_000]] = [-1, base.n_inst]; d[[10, 11]] = [-1, -70_000]; a[[20, 499_000]] = [base.horizon, -5]
+    _, _, flags = check(dataclasses.replace(base, instance_id=k, pred_tokens=d, arrival_bucket=a))
+    assert flags & ps.PS_ST_BAD_RECORD
+    r = base.rate.copy(); r[129] = 0
+    check(dataclasses.replace(base, rate=r))
+    for n_inst, horizon in [(1200, 600), (129, 1024), (256, 598), (300, 64)]:
+        print(f"anticipator any order K={n_inst} Hz={horizon}", flush=True)
+        n = 300_000
+        inp = wl.AnticipatorInputs(rng.integers(0, 3000, n, dtype=np.int32), rng.integers(0, n_inst, n, dtype=np.int32),
+                                   rng.integers(0, horizon, n, dtype=np.int32),
+                                   rng.integers(20, 200, n_inst, dtype=np.int32), n_inst, horizon)
+        check(inp)
+
+
 def test_accumulates_into_existing_map():
     inp = wl.make_anticipator_inputs("medium", seed=2, n=5000)
     rng = np.random.default_rng(0)
