@@ -29,8 +29,8 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 # step), from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; profiles/production_gemm_traffic.txt)
 # scaled by what the same counters read for a 1 GiB elementwise copy (x2.0 and x1.0).  Valid only for
 # the kernel source it was measured on: reported as null once that file has changed.
-GEMM_TRAFFIC = {"source_sha256_16": "5606705f98f6f006", "workload": "production",
-                "fetch_bytes": 23.150e9, "write_bytes": 10.116e9}
+GEMM_TRAFFIC = {"source_sha256_16": "2235e98ece3ba0d0", "workload": "production",
+                "fetch_bytes": 23.077e9, "write_bytes": 10.115e9}
 
 
 def measured_gemm_traffic(workload: str):
