@@ -407,6 +407,24 @@ def main() -> int:
                         "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
                         "records_per_s": args.stream_records / call_s}
             del sp, si, sa, sr, sload, sovf, sws
+        # yardstick: a kernel that only reads a buffer of the stream's size (three int32 per record)
+        buf = torch.randint(0, 1 << 30, (3 * ((args.stream_records + 3) // 4 * 4),), dtype=torch.int32, device=dev)
+        sink = torch.zeros(1, dtype=torch.int64, device=dev)
+        for _ in range(2):
+            ps.ps_profile_stream_read(buf, sink)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            ps.ps_profile_stream_read(buf, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        rd_s = e0.elapsed_time(e1) * 1e-3 / 10
+        rd_gbs = buf.numel() * 4 / rd_s / 1e9
+        out["stream_read_yardstick"] = {"bytes": buf.numel() * 4, "ms_per_call": 1e3 * rd_s, "GB/s": rd_gbs,
+                                        "frac_of_peak": rd_gbs / PEAK_HBM_GBS}
+        for key in ("anticipator", "anticipator_by_arrival"):
+            out[key]["frac_of_read_only_kernel"] = out[key]["achieved"] / rd_gbs
+        del buf, sink
 
     # ---- look-ahead map in KV-token units on a long record stream -----------------------------------
     if args.stream_records > 0:

@@ -290,6 +290,14 @@ int ps_profile_read(ps_model* model, void* hip_stream, double* ms /*host*/, int6
  * nominal peak clock.  Errors: PS_EINVAL, PS_EHIP. */
 int ps_profile_clock(ps_model* model, void* hip_stream, double* core_ghz /*host*/);
 
+/* Bandwidth yardstick for benchmarks: enqueue one kernel that reads `bytes` bytes at `data` (device, 16-byte
+ * aligned, bytes a multiple of 16) once and XORs the buffer's 64-bit words into *sink (device; accumulated
+ * into, so clear it first to get the buffer's XOR).  It does what the anticipator's record kernels
+ * (Sec. 3.4.1) do to their input and nothing else, so its rate is the ceiling such a kernel can be read
+ * against on a given machine.  Allocates nothing.  Errors: PS_EINVAL (null pointer, negative or unaligned
+ * size, unaligned data), PS_EHIP. */
+int ps_profile_stream_read(const void* data /*device*/, int64_t bytes, uint64_t* sink /*device*/, void* hip_stream);
+
 /* Wait for `hip_stream` and copy a device ps_status to *out (host). */
 int ps_status_read(const ps_status* status /*device*/, void* hip_stream, ps_status* out /*host*/);
 

@@ -21,7 +21,7 @@ PS_ST_BAD_TOKEN, PS_ST_BAD_LENGTH, PS_ST_NAN, PS_ST_BAD_RECORD, PS_ST_RANGE = 0x
 
 EXPORTS = ["ps_model_load", "ps_model_free", "ps_model_get_info", "ps_workspace_bytes", "ps_predict_load",
            "ps_anticipate_workspace_bytes", "ps_anticipate", "ps_anticipate_static", "ps_status_read", "ps_strerror",
-           "ps_profile_enable", "ps_profile_read", "ps_profile_clock",
+           "ps_profile_enable", "ps_profile_read", "ps_profile_clock", "ps_profile_stream_read",
            "ps_lookahead_workspace_bytes", "ps_lookahead_update", "ps_scaler_scan", "ps_route", "ps_forecast"]
 PS_FAMILIES = ["embed", "gemm", "attention", "layernorm", "head", "refine"]
 
@@ -87,6 +87,8 @@ def load_library() -> ctypes.CDLL:
     lib.ps_profile_read.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.ps_profile_clock.restype = ctypes.c_int
     lib.ps_profile_clock.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.ps_profile_stream_read.restype = ctypes.c_int
+    lib.ps_profile_stream_read.argtypes = [vp, ctypes.c_int64, vp, vp]
     lib.ps_strerror.restype = ctypes.c_char_p
     lib.ps_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -156,6 +158,14 @@ def ps_profile_clock(model: Model) -> float:
     ghz = ctypes.c_double(0.0)
     _check(load_library().ps_profile_clock(model.handle, _stream(), ctypes.byref(ghz)), "ps_profile_clock")
     return float(ghz.value)
+
+
+def ps_profile_stream_read(data: torch.Tensor, sink: torch.Tensor, nbytes: Optional[int] = None) -> None:
+    """Enqueue the read-only yardstick kernel over the first nbytes of `data` (all of it by default); the XOR
+    of its 64-bit words is accumulated into sink[0] (int64 / uint64 device tensor)."""
+    n = data.numel() * data.element_size() if nbytes is None else int(nbytes)
+    _check(load_library().ps_profile_stream_read(data.data_ptr(), n, sink.data_ptr(), _stream()),
+           "ps_profile_stream_read")
 
 
 def ps_workspace_bytes(model: Model, max_tokens: int, max_req: int) -> int:

@@ -14,7 +14,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpreserve.so")
 
 SOURCES = ["api.hip", "model_file.cpp", "rowops.hip", "encoder_f32.hip", "encoder_bf16.hip", "gemm_bf16.hip", "skinny_gemm.hip", "attention_bf16.hip",
-           "anticipate.hip", "lookahead.hip", "scaler.hip", "router.hip", "forecaster.hip"]
+           "anticipate.hip", "lookahead.hip", "scaler.hip", "router.hip", "forecaster.hip", "stream_read.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 

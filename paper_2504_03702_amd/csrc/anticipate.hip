@@ -220,6 +220,8 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_scatter_kernel(
     auto load_full = [&](int64_t blk) {
         Block b;
         const int64_t idx = min(blk, last_full) + lane * 4;
+        // plain loads: the four row groups of a slice run on one XCD and share the slice through its L2 (with
+        // the non-temporal hint the other three groups fetch it again: 0.258 against 0.225 ms on 44.1 M records)
         const int4 kv = *(const int4*)(instance_id + idx);
         const int4 dv = *(const int4*)(pred_tokens + idx);
         const int4 av = *(const int4*)(arrival_bucket + idx);
@@ -420,9 +422,9 @@ __global__ __launch_bounds__(kScatterThreads) void anticipate_window_kernel(
     auto load_full = [&](int64_t blk) {
         Blk b;
         const int64_t idx = min(blk, last_full) + lane * 4;
-        b.k = *(const int4*)(instance_id + idx);
-        b.d = *(const int4*)(pred_tokens + idx);
-        b.a = *(const int4*)(arrival_bucket + idx);
+        b.k = load_stream_int4(instance_id + idx);
+        b.d = load_stream_int4(pred_tokens + idx);
+        b.a = load_stream_int4(arrival_bucket + idx);
         return b;
     };
     auto process = [&](const Blk& b, int64_t blk) {

@@ -185,9 +185,9 @@ __global__ __launch_bounds__(kBinThreads) void lookahead_bin_kernel(
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
             const int64_t r = base + ((int64_t)u * kBinThreads + tid) * 4;
-            vk[u] = *(const int4*)(instance_id + r); vs[u] = *(const int4*)(start_iter + r);
-            vp[u] = *(const int4*)(prompt_tokens + r); vb[u] = *(const int4*)(i_begin + r);
-            ve[u] = *(const int4*)(i_end + r); vg[u] = *(const int4*)(sign + r);
+            vk[u] = load_stream_int4(instance_id + r); vs[u] = load_stream_int4(start_iter + r);
+            vp[u] = load_stream_int4(prompt_tokens + r); vb[u] = load_stream_int4(i_begin + r);
+            ve[u] = load_stream_int4(i_end + r); vg[u] = load_stream_int4(sign + r);
         }
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
