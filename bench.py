@@ -340,6 +340,21 @@ def main() -> int:
         return 1
     ms_per_step = 1e3 * dt / args.steps
 
+    # the two map updates of a step at the batch's own size are launch-latency bound: their time per call
+    def call_us(fn, reps=50):
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return 1e3 * a.elapsed_time(b) / reps
+    ant_us = call_us(lambda: ps.ps_anticipate(pred_t, inst, arr, rate, ant.n_inst, ant.horizon, load, ovf, aws, status))
+    la_us = call_us(lambda: ps.ps_lookahead_update(la_inst, la_start, la_prompt, la_zero, pred_t, la_sign, la.n_inst,
+                                                   la.map_len, la_kv, la_ovf, la_ws, status=status))
+
     gemm_flops, attn_flops = encoder_flops(cfg, lengths)
     gemm_ms, gemm_launches = prof["gemm"]
     out = {
@@ -351,6 +366,7 @@ def main() -> int:
                    "algorithmic_tflop_per_step": (gemm_flops + attn_flops) / 1e12},
         "encoder_mfma_frac": (gemm_flops + attn_flops) / (dt / args.steps) / (PEAK_BF16_TFLOPS * 1e12),
         "kernel_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
+        "map_updates_us_per_call": {"records": n_req, "anticipate": ant_us, "lookahead_update": la_us},
     }
     if cfg.dtype == wl.DTYPE_BF16 and gemm_launches:
         # dominant kernel: the bf16 MFMA GEMM (4 launches per layer); algorithmic flops per launch =
@@ -407,6 +423,29 @@ def main() -> int:
                         "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
                         "records_per_s": args.stream_records / call_s}
             del sp, si, sa, sr, sload, sovf, sws
+        # how the rate builds up with the record count (arbitrary order)
+        ramp = []
+        for n_r in (1 << 20, 1 << 24):
+            if n_r >= args.stream_records:
+                continue
+            r_in = wl.make_anticipator_inputs("stream", seed=0, n=n_r)
+            rp, ri, ra, rr = t32(r_in.pred_tokens), t32(r_in.instance_id), t32(r_in.arrival_bucket), t32(r_in.rate)
+            rload = torch.zeros(r_in.n_inst * r_in.horizon, dtype=torch.int32, device=dev)
+            rovf = torch.zeros(r_in.n_inst, dtype=torch.int64, device=dev)
+            rws = ps.alloc_workspace(ps.ps_anticipate_workspace_bytes(n_r, r_in.n_inst, r_in.horizon), dev)
+            for _ in range(2):
+                ps.ps_anticipate(rp, ri, ra, rr, r_in.n_inst, r_in.horizon, rload, rovf, rws, status)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                ps.ps_anticipate(rp, ri, ra, rr, r_in.n_inst, r_in.horizon, rload, rovf, rws, status)
+            e1.record()
+            torch.cuda.synchronize()
+            r_s = e0.elapsed_time(e1) * 1e-3 / 20
+            ramp.append({"records": n_r, "ms_per_call": 1e3 * r_s,
+                         "GB/s": (12.0 * n_r + 8.0 * r_in.n_inst * r_in.horizon) / r_s / 1e9})
+            del rp, ri, ra, rr, rload, rovf, rws
+        out["anticipator"]["ramp"] = ramp
         # yardstick: a kernel that only reads a buffer of the stream's size (three int32 per record)
         buf = torch.randint(0, 1 << 30, (3 * ((args.stream_records + 3) // 4 * 4),), dtype=torch.int32, device=dev)
         sink = torch.zeros(1, dtype=torch.int64, device=dev)
