@@ -256,6 +256,9 @@ def main() -> int:
                     help="timed micro-batches of the latency leg, after a tenth as many warm-up ones (0 = skip)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run one plain elementwise copy of this many MiB (a known traffic for counter runs)")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="instead of the benchmark: time the vendor library's bf16 GEMM (torch linear, bias only) on the "
+                         "workload's four map shapes, as a yardstick for this library's GEMM kernel, and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
@@ -280,6 +283,29 @@ def main() -> int:
         del src, dst
     model_kind, prompt_kind, ant_kind, desc = WORKLOADS[args.workload]
     cfg = wl.MODELS[model_kind].resolved()
+    if args.vendor_gemm:
+        # the rows one step's maps run over, random operands; the library's own kernel is chosen by torch
+        rows = (int(wl.make_prompts(prompt_kind, seed=0).valid_lengths().sum()) + 255) // 256 * 256
+        H, F = cfg.hidden, cfg.ffn
+        res = []
+        gen = torch.Generator(device=dev).manual_seed(0)
+        for name, K, N in (("qkv", H, 3 * H), ("o_proj", H, H), ("ffn1", H, F), ("ffn2", F, H)):
+            xa = torch.randn(rows, K, device=dev, generator=gen).to(torch.bfloat16)
+            wb = (torch.randn(N, K, device=dev, generator=gen) * 0.02).to(torch.bfloat16)
+            bb = torch.zeros(N, device=dev, dtype=torch.bfloat16)
+            for _ in range(2):
+                torch.nn.functional.linear(xa, wb, bb)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                torch.nn.functional.linear(xa, wb, bb)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            res.append({"map": name, "rows": rows, "K": K, "N": N, "ms": ms, "TFLOP/s": 2.0 * rows * K * N / ms / 1e9})
+            del xa, wb, bb
+        print(json.dumps({"vendor_gemm": res, "workload": args.workload, "dtype": "bf16"}))
+        return 0
 
     tmp = tempfile.mkdtemp(prefix="ps_bench_")
     model_path = os.path.join(tmp, f"{model_kind}.bin")
